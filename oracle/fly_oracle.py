@@ -1,0 +1,410 @@
+"""CPU oracle for the FLy verification step.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, fp64 restatement of what the verification step computes,
+written from the FLy paper (arxiv 2511.22972) and from the textbook definition
+of a pre-norm Llama-style decoder.  It exists so that the HIP kernels have
+something independent to be compared with.  It shares no code, table or
+helper with the HIP path and must never be imported by the product package;
+only tests, the smoke check and the benchmark's CPU-baseline leg use it.
+
+Parts and what fixes them:
+  * acceptance rule            -- paper Sec. 2.1-2.2, Eqs. 2-11, and Algorithm 1;
+                                  three independently written forms.
+  * row statistics             -- Eq. 1 (softmax, argmax) and Eq. 5 (normalised
+                                  entropy), literal sums in fp64.
+  * decoder forward            -- the paper treats the target model as a black
+                                  box (Sec. 2.1, Algorithm 1 step 2); the
+                                  arithmetic here is the standard pre-RMSNorm,
+                                  rotary, grouped-query, SwiGLU decoder.
+
+Pins (tests/test_oracle_*.py): closed forms of Eq. 5, the limit statements of
+the ablation section (theta=1, theta=0, W=0), the boundary rule j+W>K, brute
+force over all mismatch/gate patterns, scipy's logsumexp/entropy, torch's
+scaled_dot_product_attention, and the Hugging Face Llama implementation run
+in fp64 on a tiny model.  Free-running parity of the full forward at bf16
+depth is pinned only up to the stated logit tolerance (see `Numerics`).
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+# ==========================================================================
+# 1. Acceptance rule (paper Sec. 2.1-2.2).  Positions are 1-based as in the
+#    paper: draft[j-1] is y-hat_j, target[j-1] is y_j (j = 1..K+1),
+#    h[j-1] is h_j.
+# ==========================================================================
+
+
+def match_indicator(draft: Sequence[int], target: Sequence[int]) -> List[int]:
+    """Delta_i = 1[draft_i == target_i], 1 <= i <= K  (Eq. 2)."""
+    K = len(draft)
+    return [1 if int(draft[i]) == int(target[i]) else 0 for i in range(K)]
+
+
+def s_standard(delta: Sequence[int]) -> int:
+    """Exact-match speculative decoding count (Eq. 3): the index of the first
+    mismatch, or K+1 when every draft matches."""
+    K = len(delta)
+    for i in range(1, K + 1):
+        if delta[i - 1] == 0:
+            return i
+    return K + 1
+
+
+def accept_equations(delta: Sequence[int], h: Sequence[float], theta: float,
+                     W: int) -> Tuple[int, int, int]:
+    """(s_gate, s_defer, s_FLy) computed set-wise from Eqs. 4-11.
+
+    Every quantity is built for all j in J first; the minima are taken last.
+    """
+    K = len(delta)
+    J = [j for j in range(1, K + 1) if delta[j - 1] == 0]  # Eq. 4
+
+    # Eq. 6: gate label per mismatch.
+    gate = {j: ("Strict" if h[j - 1] < theta else "Defer") for j in J}
+    strict = [j for j in J if gate[j] == "Strict"]
+    s_gate = min(strict) if strict else K + 1  # Eq. 7
+
+    # Eqs. 8-9.  The window must fit inside the K drafts (boundary rule of
+    # Sec. 2.2); that is tested before the sum so no Delta beyond K is read.
+    decide = {}
+    for j in J:
+        if h[j - 1] >= theta and j + W <= K:
+            n_w = sum(1 - delta[i - 1] for i in range(j + 1, j + W + 1))  # Eq. 8
+            decide[j] = "Accept" if n_w == 0 else "Reject"
+        else:
+            decide[j] = "Reject"
+    rejected = [j for j in J if decide[j] == "Reject"]
+    s_defer = min(rejected) if rejected else K + 1  # Eq. 10
+
+    return s_gate, s_defer, min(s_gate, s_defer)  # Eq. 11
+
+
+def accept_algorithm(draft: Sequence[int], target: Sequence[int], h: Sequence[float],
+                     theta: float, W: int) -> Tuple[int, List[int]]:
+    """One round of Algorithm 1, steps 2-4: walk the mismatches in ascending
+    order and stop at the first rejected one.
+
+    Returns (s, emitted): s is the paper's accepted count for the round (it
+    includes the correction or bonus token) and `emitted` the s tokens
+    appended to the sequence.
+    """
+    K = len(draft)
+    delta = match_indicator(draft, target)
+    for j in range(1, K + 1):
+        if delta[j - 1] == 1:
+            continue
+        if h[j - 1] < theta:  # strict: reject here
+            return j, [int(t) for t in draft[: j - 1]] + [int(target[j - 1])]
+        if j + W > K:  # window does not fit: reject here
+            return j, [int(t) for t in draft[: j - 1]] + [int(target[j - 1])]
+        later_mismatches = 0
+        for i in range(j + 1, j + W + 1):
+            later_mismatches += 1 - delta[i - 1]
+        if later_mismatches != 0:
+            return j, [int(t) for t in draft[: j - 1]] + [int(target[j - 1])]
+        # mismatch at j is kept (as the draft's token); go on to the next one
+    return K + 1, [int(t) for t in draft] + [int(target[K])]
+
+
+def accept_predicate(delta: Sequence[int], h: Sequence[float], theta: float, W: int) -> int:
+    """Third form: a per-position reject predicate, s = first position where
+    it holds (K+1 if none).
+
+        rej(j) = not Delta_j and (h_j < theta  or  j + W > K
+                                  or  exists i in (j, j+W]: not Delta_i)
+    """
+    K = len(delta)
+    mism = 0
+    for j in range(1, K + 1):
+        if delta[j - 1] == 0:
+            mism |= 1 << j
+    for j in range(1, K + 1):
+        if not (mism >> j) & 1:
+            continue
+        if h[j - 1] < theta or j + W > K:
+            return j
+        window_bits = ((1 << W) - 1) << (j + 1)
+        if mism & window_bits:
+            return j
+    return K + 1
+
+
+def accept_block(draft, target, h, theta: float, W: int) -> Dict[str, np.ndarray]:
+    """Batch wrapper in the exported convention.
+
+    draft [B,K] int, target [B,K+1] int, h [B,K+1] (only the first K columns
+    are used; the bonus row takes no part in the rule).  The gate compares in
+    float32, the type the entropies are produced in.
+    Returns accept_len = s-1 (draft tokens kept), next_token = y_s,
+    n_loose = mismatching drafts kept, s = the paper's count.
+    """
+    draft = np.asarray(draft)
+    target = np.asarray(target)
+    h32 = np.asarray(h, dtype=np.float32)
+    th32 = np.float32(theta)
+    B, K = draft.shape
+    out = {k: np.zeros(B, dtype=np.int32) for k in ("accept_len", "next_token", "n_loose", "s")}
+    for b in range(B):
+        s, emitted = accept_algorithm(draft[b], target[b], h32[b], th32, W)
+        delta = match_indicator(draft[b], target[b])
+        out["s"][b] = s
+        out["accept_len"][b] = s - 1
+        out["next_token"][b] = emitted[-1]
+        out["n_loose"][b] = sum(1 - delta[j - 1] for j in range(1, s))
+    return out
+
+
+# ==========================================================================
+# 2. Row statistics (Eq. 1, Eq. 5): literal definitions in fp64.
+# ==========================================================================
+
+
+def row_statistics(logits) -> Dict[str, float]:
+    """Statistics of one logit row (fp64).
+
+    argmax  -- lowest index among maxima (Eq. 1)
+    margin  -- largest minus second-largest logit (diagnostic for near ties)
+    lse     -- log sum exp
+    H       -- Shannon entropy in nats, the literal -sum p log p of Eq. 5;
+               entries with p == 0 contribute 0
+    h       -- H / log V, V = number of columns (Eq. 5)
+    p_top1  -- probability of the argmax token
+    """
+    l = np.asarray(logits, dtype=np.float64)
+    V = l.shape[0]
+    y = int(np.argmax(l))  # numpy returns the first maximal index
+    m = l[y]
+    p_unnorm = np.exp(l - m)
+    Z = p_unnorm.sum()
+    p = p_unnorm / Z
+    nz = p > 0
+    H = float(-(p[nz] * np.log(p[nz])).sum())
+    if V > 1:
+        rest = np.delete(l, y)
+        margin = float(m - rest.max())
+    else:
+        margin = float("inf")
+    return {"argmax": y, "margin": margin, "lse": float(m + math.log(Z)), "H": H,
+            "h": H / math.log(V) if V > 1 else 0.0, "p_top1": float(p[y])}
+
+
+def block_statistics(logits: np.ndarray) -> Dict[str, np.ndarray]:
+    """row_statistics over the rows of an [M, V] array."""
+    rows = [row_statistics(r) for r in np.asarray(logits)]
+    out = {}
+    for key in ("argmax", "margin", "lse", "H", "h", "p_top1"):
+        out[key] = np.array([r[key] for r in rows], dtype=np.int64 if key == "argmax" else np.float64)
+    return out
+
+
+# ==========================================================================
+# 3. Decoder forward (textbook pre-norm decoder; shapes come from the
+#    workload, the paper only says "a single forward pass", Sec. 2.1).
+# ==========================================================================
+
+
+def round_to_bf16(x: torch.Tensor) -> torch.Tensor:
+    """Value-preserving fp64 tensor whose entries are the bf16 roundings of x.
+
+    Two steps, as on the device: the fp64 value is first rounded to fp32 (the
+    type the accumulators are held in), then to bf16 by round-to-nearest-even
+    on the upper 16 bits.  NaNs are not expected and not handled.
+    """
+    a = x.detach().to(torch.float64).contiguous().numpy().astype(np.float32)
+    u = a.view(np.uint32).astype(np.uint64)
+    bias = np.uint64(0x7FFF) + ((u >> np.uint64(16)) & np.uint64(1))
+    r = ((u + bias) & np.uint64(0xFFFF0000)).astype(np.uint32)
+    return torch.from_numpy(r.view(np.float32).astype(np.float64)).view(x.shape)
+
+
+def round_to_f32(x: torch.Tensor) -> torch.Tensor:
+    return x.to(torch.float32).to(torch.float64)
+
+
+@dataclasses.dataclass
+class Numerics:
+    """Where the oracle rounds.
+
+    storage == "f32": nothing is rounded (inputs are fp32 values, all
+    arithmetic fp64).
+    storage == "bf16": the tensors the device holds in bf16 are rounded to
+    bf16 here too -- normalised activations, rotated q/k and v, the
+    unnormalised attention probabilities, the attention output, the SwiGLU
+    output -- and the rotary cos/sin tables are rounded to fp32.  The residual
+    stream, GEMM accumulators and all row statistics are never rounded.
+    """
+    storage: str = "f32"
+
+    def act(self, x: torch.Tensor) -> torch.Tensor:
+        return round_to_bf16(x) if self.storage == "bf16" else x
+
+    def table(self, x: torch.Tensor) -> torch.Tensor:
+        return round_to_f32(x) if self.storage == "bf16" else x
+
+
+def rmsnorm(x: torch.Tensor, g: torch.Tensor, eps: float) -> torch.Tensor:
+    """x / sqrt(mean(x^2) + eps) * g along the last axis."""
+    ms = (x * x).mean(dim=-1, keepdim=True)
+    return x / torch.sqrt(ms + eps) * g
+
+
+def rope_tables(positions: torch.Tensor, head_dim: int, theta: float):
+    """cos/sin of pos * theta^(-2i/hd), i = 0..hd/2-1  ->  each [n_pos, hd/2]."""
+    i = torch.arange(head_dim // 2, dtype=torch.float64)
+    inv_freq = theta ** (-2.0 * i / head_dim)
+    ang = positions.to(torch.float64)[:, None] * inv_freq[None, :]
+    return torch.cos(ang), torch.sin(ang)
+
+
+def apply_rope(x: torch.Tensor, cos: torch.Tensor, sin: torch.Tensor) -> torch.Tensor:
+    """Rotate pairs (i, i + hd/2) of x [n_pos, heads, hd] by the position angle."""
+    half = x.shape[-1] // 2
+    x1, x2 = x[..., :half], x[..., half:]
+    c, s = cos[:, None, :], sin[:, None, :]
+    return torch.cat([x1 * c - x2 * s, x2 * c + x1 * s], dim=-1)
+
+
+def silu(x: torch.Tensor) -> torch.Tensor:
+    return x / (1.0 + torch.exp(-x))
+
+
+def attention_one_sequence(q: torch.Tensor, k_all: torch.Tensor, v_all: torch.Tensor,
+                           prefix_len: int, num: Numerics) -> torch.Tensor:
+    """Causal grouped-query attention for the K+1 new rows of one sequence.
+
+    q [R, Hq, hd]; k_all, v_all [prefix_len + R, Hkv, hd] (cached prefix
+    followed by the R new rows).  Query row i sees keys 0..prefix_len+i.
+    Query head a uses KV head a // (Hq/Hkv).  Returns [R, Hq, hd].
+    """
+    R, Hq, hd = q.shape
+    T, Hkv, _ = k_all.shape
+    G = Hq // Hkv
+    out = torch.zeros(R, Hq, hd, dtype=torch.float64)
+    key_pos = torch.arange(T)
+    for a in range(Hq):
+        kh = k_all[:, a // G, :]  # [T, hd]
+        vh = v_all[:, a // G, :]
+        scores = (q[:, a, :] @ kh.T) / math.sqrt(hd)  # [R, T]
+        for i in range(R):
+            visible = key_pos <= prefix_len + i
+            s = scores[i][visible]
+            e = torch.exp(s - s.max())
+            # The device multiplies bf16 probabilities into V and normalises
+            # by the unrounded sum afterwards.
+            out[i, a, :] = (num.act(e) @ vh[visible]) / e.sum()
+    return out
+
+
+@dataclasses.dataclass
+class LayerWeights:
+    """Canonical weights of one decoder layer, all [in, out], fp64 tensors."""
+    wq: torch.Tensor
+    wk: torch.Tensor
+    wv: torch.Tensor
+    wo: torch.Tensor
+    wg: torch.Tensor
+    wu: torch.Tensor
+    wd: torch.Tensor
+    g_attn: torch.Tensor
+    g_ffn: torch.Tensor
+
+
+def decoder_layer(x: torch.Tensor, w: LayerWeights, k_prefix: torch.Tensor,
+                  v_prefix: torch.Tensor, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                  rope_theta: float, eps: float, num: Numerics):
+    """One pre-norm decoder layer over the new rows of ONE sequence.
+
+    x [R, d] residual stream; k_prefix, v_prefix [L, Hkv, hd] cached rows
+    (keys already rotated).  Row i sits at absolute position L + i.
+    Returns (x_out [R, d], k_new [R, Hkv, hd], v_new [R, Hkv, hd]); the new
+    rows are what gets appended to the cache.
+    """
+    R, d = x.shape
+    L = k_prefix.shape[0]
+    xn = num.act(rmsnorm(x, w.g_attn, eps))
+    q = (xn @ w.wq).view(R, n_q_heads, head_dim)
+    k = (xn @ w.wk).view(R, n_kv_heads, head_dim)
+    v = (xn @ w.wv).view(R, n_kv_heads, head_dim)
+    cos, sin = rope_tables(torch.arange(L, L + R), head_dim, rope_theta)
+    cos, sin = num.table(cos), num.table(sin)
+    q = num.act(apply_rope(q, cos, sin))
+    k = num.act(apply_rope(k, cos, sin))
+    v = num.act(v)
+    k_all = torch.cat([k_prefix, k], dim=0)
+    v_all = torch.cat([v_prefix, v], dim=0)
+    o = num.act(attention_one_sequence(q, k_all, v_all, L, num))
+    x = x + o.reshape(R, n_q_heads * head_dim) @ w.wo
+    xn = num.act(rmsnorm(x, w.g_ffn, eps))
+    a = num.act(silu(xn @ w.wg) * (xn @ w.wu))
+    x = x + a @ w.wd
+    return x, k, v
+
+
+def lm_head_logits(x_final_normed: torch.Tensor, w_lm: torch.Tensor,
+                   row_scale: Optional[torch.Tensor]) -> torch.Tensor:
+    """logits[m, v] = (x[m] . W_lm[:, v]) * row_scale[m]."""
+    logits = x_final_normed @ w_lm
+    if row_scale is not None:
+        logits = logits * row_scale.to(torch.float64)[:, None]
+    return logits
+
+
+def decision_statistics(logits: torch.Tensor) -> Dict[str, np.ndarray]:
+    """Row statistics with the integer decision taken in float32.
+
+    The argmax is taken over the logits rounded to float32 (the precision the
+    device decides in); everything else is fp64 on the unrounded logits.
+    """
+    l64 = logits.numpy()
+    stats = block_statistics(l64)
+    l32 = l64.astype(np.float32)
+    stats["argmax"] = np.argmax(l32, axis=1).astype(np.int64)
+    return stats
+
+
+def verify_block(tokens, embed: torch.Tensor, layers: Sequence[LayerWeights],
+                 g_final: torch.Tensor, w_lm: torch.Tensor,
+                 kv_prefix: Sequence[Tuple[torch.Tensor, torch.Tensor]],
+                 row_scale: Optional[torch.Tensor], *, n_q_heads: int, n_kv_heads: int,
+                 head_dim: int, rope_theta: float, eps: float, theta: float, W: int,
+                 storage: str = "f32", return_logits: bool = False) -> Dict[str, np.ndarray]:
+    """The whole verification step for B sequences (Sec. 2.1-2.2, Alg. 1 steps 2-4).
+
+    tokens [B, K+1] = (y_{-1}, draft_1..draft_K) per sequence.
+    kv_prefix[layer] = (k [B, L, Hkv, hd], v [B, L, Hkv, hd]).
+    All tensors are fp64 holding values representable in the storage type.
+    """
+    num = Numerics(storage)
+    tokens = np.asarray(tokens)
+    B, R = tokens.shape
+    K = R - 1
+    d = embed.shape[1]
+    logits_all = []
+    new_kv = []
+    for b in range(B):
+        x = embed[torch.from_numpy(tokens[b].astype(np.int64))].clone()
+        seq_kv = []
+        for li, w in enumerate(layers):
+            kp, vp = kv_prefix[li]
+            x, k_new, v_new = decoder_layer(x, w, kp[b], vp[b], n_q_heads, n_kv_heads,
+                                            head_dim, rope_theta, eps, num)
+            seq_kv.append((k_new, v_new))
+        xn = num.act(rmsnorm(x, g_final, eps))
+        rs = None if row_scale is None else row_scale.reshape(B, R)[b]
+        logits_all.append(lm_head_logits(xn, w_lm, rs))
+        new_kv.append(seq_kv)
+    logits = torch.stack(logits_all)  # [B, R, V]
+    stats = decision_statistics(logits.reshape(B * R, -1))
+    out = {k: v.reshape(B, R) for k, v in stats.items()}
+    acc = accept_block(tokens[:, 1:], out["argmax"], out["h"], theta, W)
+    out.update(acc)
+    out["new_kv"] = new_kv
+    if return_logits:
+        out["logits"] = logits.numpy()
+    return out
