@@ -37,7 +37,7 @@ def test_presets():
     c1 = synth.CONFIGS["c1_tiny"]
     assert sum(a * b for a, b in synth.layer_weight_shapes(c1).values()) == 724_992
     temps = synth.make_row_temperature(c1)
-    assert temps.shape == (1, 5) and set(np.round(temps.numpy().ravel(), 4)) <= {0.3, 1.0, 3.0}
+    assert temps.shape == (1, 5) and set(np.round(temps.double().numpy().ravel(), 4)) <= {0.3, 1.0, 3.0}
     c5 = synth.CONFIGS["c5_stress"]
     t5 = synth.make_row_temperature(c5).numpy()
     assert t5.min() >= 0.1 - 1e-6 and t5.max() <= 10 + 1e-5 and t5.shape == (64, 17)
