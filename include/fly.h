@@ -1,0 +1,226 @@
+/*
+ * fly.h -- C ABI of the FLy verification step on one MI355X (gfx950).
+ *
+ * FLy (Training-Free Loosely Speculative Decoding, arxiv 2511.22972) changes
+ * only how the target model verifies a block of K draft tokens.  This library
+ * is that verification step: one forward pass of a Llama-style decoder over
+ * the K+1 tokens (y_{-1}, draft_1..draft_K) against a cached prefix (paper
+ * Sec. 2.1; Algorithm 1 step 2), per-position softmax statistics (Eq. 1,
+ * Eq. 5), and the loose acceptance rule (Eqs. 2-11; Algorithm 1 steps 3-4).
+ *
+ * General conventions
+ *   - Every function returns a fly_status (0 = OK, negative = error) and never
+ *     throws, aborts, allocates or synchronises.  All GPU work is enqueued on
+ *     the caller's stream (`fly_stream` is a hipStream_t; NULL = default
+ *     stream).
+ *   - Pointers marked [device] are device memory owned by the caller and must
+ *     stay valid until the enqueued work has finished; they must be 16-byte
+ *     aligned.  Pointers marked [host] are read during the call only.
+ *   - Arguments are validated on the host before anything is enqueued; on an
+ *     error nothing has been launched.
+ *   - M = B*(K+1) rows; row m = b*(K+1) + i is position i of sequence b and
+ *     sits at absolute position kv_len[b] + i.
+ *   - dtype FLY_F32: weights, KV cache and activations are fp32.
+ *     dtype FLY_BF16: weights, KV cache and GEMM operands are bf16, the
+ *     residual stream, accumulators and all statistics are fp32.
+ */
+#ifndef FLY_H
+#define FLY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FLY_OK = 0,
+  FLY_ERR_NULL_POINTER = -1,   /* a required pointer is NULL */
+  FLY_ERR_BAD_SHAPE = -2,      /* B, M, d, F, V, heads ... out of range or not tileable */
+  FLY_ERR_K_RANGE = -3,        /* K outside [1, 63] (one wavefront holds a block) */
+  FLY_ERR_WINDOW = -4,         /* W < 0 */
+  FLY_ERR_THETA = -5,          /* theta is NaN */
+  FLY_ERR_DTYPE = -6,          /* unknown fly_dtype */
+  FLY_ERR_HEAD_DIM = -7,       /* head_dim not supported for this dtype */
+  FLY_ERR_ALIGNMENT = -8,      /* a device pointer is not 16-byte aligned */
+  FLY_ERR_WORKSPACE = -9,      /* workspace NULL or smaller than the query says */
+  FLY_ERR_KV_CAPACITY = -10,   /* max_kv_len + K + 1 exceeds the cache capacity */
+  FLY_ERR_LAUNCH = -11         /* the HIP runtime refused a launch */
+} fly_status;
+
+typedef enum { FLY_F32 = 0, FLY_BF16 = 1 } fly_dtype;
+
+typedef void* fly_stream; /* hipStream_t */
+
+/* Geometry of the target model (shapes only; the paper fixes none of them). */
+typedef struct {
+  int32_t n_layers;
+  int32_t d;          /* hidden size */
+  int32_t n_q_heads;  /* Hq */
+  int32_t n_kv_heads; /* Hkv, divides Hq */
+  int32_t head_dim;   /* hd: 64 or 128 for FLY_F32, 128 for FLY_BF16 */
+  int32_t ffn;        /* F, SwiGLU width */
+  int32_t vocab;      /* V = |vocabulary| of Eq. 5 */
+  int32_t dtype;      /* fly_dtype */
+  float rms_eps;
+  float rope_theta;
+} fly_model_desc;
+
+/*
+ * Packed weights of one decoder layer [device].  Each matrix was produced by
+ * fly_pack_weight from a canonical row-major [in, out] matrix:
+ *   w_qkv     [d, (Hq+2Hkv)*hd]  columns = q heads, then k heads, then v heads
+ *   w_o       [Hq*hd, d]
+ *   w_gateup  [d, 2F]            16-column tiles alternate gate, up, gate, up ...
+ *   w_down    [F, d]
+ *   g_attn, g_ffn  RMSNorm gains [d] in the model dtype
+ */
+typedef struct {
+  const void* w_qkv;
+  const void* w_o;
+  const void* w_gateup;
+  const void* w_down;
+  const void* g_attn;
+  const void* g_ffn;
+} fly_layer_weights;
+
+typedef struct {
+  const void* embed;                /* [device] [V, d] row-major, model dtype */
+  const fly_layer_weights* layers;  /* [host] array of n_layers entries */
+  const void* g_final;              /* [device] final RMSNorm gain [d] */
+  const void* w_lm;                 /* [device] packed [d, V] */
+} fly_weights;
+
+/*
+ * KV cache.  Per layer, keys are [B, Hkv, capacity, hd] and values are stored
+ * transposed, [B, Hkv, hd, capacity], both in the model dtype; keys are held
+ * already rotated.  Rows 0..kv_len[b]-1 of sequence b are the cached prefix.
+ * The verification step writes rows kv_len[b]..kv_len[b]+K of every layer and
+ * reads rows 0..kv_len[b]+K.  capacity must be a multiple of 64.
+ */
+typedef struct {
+  void* const* k_layers;   /* [host] n_layers device pointers */
+  void* const* v_layers;   /* [host] n_layers device pointers */
+  const int32_t* kv_len;   /* [device] int32 [B] */
+  int32_t capacity;        /* rows allocated per sequence */
+  int32_t max_kv_len;      /* host-side bound: kv_len[b] <= max_kv_len for all b */
+} fly_kv_cache;
+
+/* Outputs of fly_verify_block, all [device]; the last three may be NULL. */
+typedef struct {
+  int32_t* accept_len;   /* [B]  draft tokens kept = s_FLy - 1  (Eq. 11) */
+  int32_t* next_token;   /* [B]  y_s: correction token, or the bonus token when all K are kept */
+  int32_t* kv_len_out;   /* [B]  kv_len + accept_len + 1 (rows of the cache that stay valid) */
+  int32_t* argmax;       /* [B, K+1] target tokens y_1..y_{K+1} (Eq. 1) */
+  float* h_norm;         /* [B, K+1] normalised entropy (Eq. 5) */
+  float* p_top1;         /* [B, K+1] probability of the argmax token */
+  float* lse;            /* [B, K+1] log-sum-exp of the row, nullable */
+  int32_t* n_loose;      /* [B] mismatching drafts that were kept, nullable */
+  float* hidden_out;     /* [M, d] fp32 residual stream after the last layer, nullable */
+} fly_verify_out;
+
+const char* fly_strerror(fly_status s);
+
+/*
+ * Launch-shape knobs for experiments (process-wide, not thread-safe):
+ *   "gemm_nt"      16-column weight tiles per wavefront: 1, 2, 4; 0 = automatic
+ *   "gemm_splits"  split-K factor of the projections: 1..16; 0 = automatic
+ *   "target_wgs"   workgroups a launch aims for (default 512)
+ * Workspace sizes depend on them: query again after a change.
+ */
+fly_status fly_set_tuning(const char* key, int32_t value);
+
+/*
+ * Weight packing (one-time, at load).  The packed layout is this library's own:
+ *   FLY_BF16: tiles of 16 output columns x 32 input rows, each stored as the 64
+ *             lanes x 8 values one matrix-core operand load wants, tiles of
+ *             one 16-column strip contiguous along the input dimension.
+ *             Requires k_in % 32 == 0.
+ *   FLY_F32:  row-major [k_in, n_dst].
+ * Source column tile j (columns 16j..16j+15 of src [k_in, n_src] row-major)
+ * lands at destination column tile tile_offset + j*tile_stride of a
+ * destination that is n_dst columns wide.  n_src and n_dst must be multiples
+ * of 16.  fly_packed_weight_bytes gives the destination size.
+ */
+fly_status fly_packed_weight_bytes(int64_t k_in, int64_t n_dst, int32_t dtype, size_t* bytes);
+fly_status fly_pack_weight(const void* src /*[device]*/, int64_t k_in, int64_t n_src, int32_t dtype,
+                           void* dst /*[device]*/, int64_t n_dst, int64_t tile_offset,
+                           int64_t tile_stride, fly_stream stream);
+
+/* Workspace sizes (bytes) for the calls below. */
+fly_status fly_workspace_bytes(const fly_model_desc* desc, int32_t B, int32_t K,
+                               int32_t max_kv_len, size_t* bytes);
+fly_status fly_lmhead_workspace_bytes(int32_t M, int32_t d, int32_t V, int32_t dtype, size_t* bytes);
+
+/*
+ * The verification step (paper Sec. 2.1-2.2; Algorithm 1 steps 2-4).
+ *   tokens     [device] int32 [B, K+1] = y_{-1}, draft_1..draft_K per sequence
+ *   row_scale  [device] float [B*(K+1)] multiplier applied to each row's logits
+ *              before the statistics (1/temperature of the synthetic
+ *              workloads), or NULL for 1
+ *   theta, W   entropy threshold and deferred-window length of Eqs. 6-9
+ * Runs embedding, n_layers decoder layers (appending K+1 rows per layer to the
+ * KV cache), the final norm, the LM head with fused row statistics -- the
+ * logits are never written to memory -- and the acceptance rule.
+ * Errors: see fly_status; K > 63 is FLY_ERR_K_RANGE.
+ */
+fly_status fly_verify_block(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                            const int32_t* tokens, const float* row_scale, int32_t B, int32_t K,
+                            float theta, int32_t W, const fly_verify_out* out, void* workspace,
+                            size_t workspace_bytes, fly_stream stream);
+
+/*
+ * Decoder layers [layer_begin, layer_end) applied in place to a residual
+ * stream x [device] fp32 [M, d] (the middle of fly_verify_block, exposed for
+ * per-layer checks and per-layer timing).  Uses the same workspace.
+ */
+fly_status fly_decoder_layers(const fly_model_desc* desc, const fly_weights* w,
+                              const fly_kv_cache* kv, float* x, int32_t layer_begin,
+                              int32_t layer_end, int32_t B, int32_t K, void* workspace,
+                              size_t workspace_bytes, fly_stream stream);
+
+/*
+ * LM head with fused row statistics (Eq. 1 and Eq. 5).
+ *   hidden  [device] [M, d] in the model dtype (already normalised)
+ *   w_lm    [device] packed [d, V]
+ * Outputs [device]: argmax int32 [M] (lowest index on ties), p_top1 float [M],
+ * h_norm float [M] = H / ln V, lse float [M] (nullable).
+ * V must be a multiple of 16; d a multiple of 32 for FLY_BF16.
+ */
+fly_status fly_lmhead_entropy_argmax(const void* hidden, const void* w_lm, const float* row_scale,
+                                     int32_t M, int32_t d, int32_t V, int32_t dtype,
+                                     int32_t* argmax, float* p_top1, float* h_norm, float* lse,
+                                     void* workspace, size_t workspace_bytes, fly_stream stream);
+
+/*
+ * FLy's loose acceptance rule (Eqs. 2-11; Algorithm 1 steps 3-4).
+ *   draft       [device] int32 [B, K]      draft_1..draft_K
+ *   tgt_argmax  [device] int32 [B, K+1]    y_1..y_{K+1}
+ *   h_norm      [device] float [B, K+1]    h_1..h_{K+1} (the last is unused)
+ * A mismatch at j is rejected when h_j < theta, when j + W > K, or when any
+ * of positions j+1..j+W mismatches; s is the first rejected position, or K+1.
+ * Outputs [device]: accept_len[b] = s-1, next_token[b] = y_s, n_loose[b]
+ * (nullable) = number of mismatching drafts among the kept ones.
+ * 1 <= K <= 63, W >= 0, theta not NaN (theta > 1 gives exact-match decoding).
+ */
+fly_status fly_accept(const int32_t* draft, const int32_t* tgt_argmax, const float* h_norm,
+                      int32_t B, int32_t K, float theta, int32_t W, int32_t* accept_len,
+                      int32_t* next_token, int32_t* n_loose, fly_stream stream);
+
+/*
+ * (K+1)-query causal grouped-query attention against the cache of one layer
+ * (exposed for the long-cache workload and for per-kernel timing).
+ *   q  [device] [M, Hq*hd] model dtype, already rotated
+ *   o  [device] [M, Hq*hd] model dtype
+ * Reads cache rows 0..kv_len[b]+i for query i; the K+1 new rows must already
+ * be in the cache.  Workspace as for fly_verify_block.
+ */
+fly_status fly_attention(const fly_model_desc* desc, const fly_kv_cache* kv, int32_t layer,
+                         const void* q, void* o, int32_t B, int32_t K, void* workspace,
+                         size_t workspace_bytes, fly_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLY_H */

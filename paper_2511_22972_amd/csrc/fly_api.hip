@@ -1,0 +1,485 @@
+// C ABI of the FLy verification step: argument validation, workspace
+// planning and the launch sequence.  See include/fly.h for the contract.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "fly_common.h"
+
+namespace {
+
+// --- tuning knobs (0 = automatic); set through fly_set_tuning ---------------
+int g_force_nt = 0;
+int g_force_splits = 0;
+int g_target_wgs = 512;
+
+inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline size_t elem_size(int dtype) { return dtype == FLY_BF16 ? 2 : 4; }
+
+int pick_mt(int rows) {
+  int tiles = (rows + 15) / 16;
+  const int opts[5] = {1, 2, 3, 5, 9};
+  for (int i = 0; i < 5; ++i)
+    if (tiles <= opts[i]) return opts[i];
+  return 9;
+}
+
+// Plan of one bf16 GEMM: enough workgroups to fill 256 compute units twice,
+// split-K only when the output is too narrow to do that alone.
+GemmPlan plan_gemm(int M, int N, int Kd, bool allow_split, bool need_even_nt) {
+  GemmPlan p;
+  p.mblocks = (M + 143) / 144;
+  p.mt = p.mblocks > 1 ? 9 : pick_mt(M);
+  int ntiles = N / 16;
+  int nchunks = (Kd / 32 + 3) / 4;
+  int nt = 4;
+  if (g_force_nt) {
+    nt = g_force_nt;
+  } else {
+    // widest wave tile that still yields the wanted number of workgroups
+    while (nt > 1 && (ntiles + 4 * nt - 1) / (4 * nt) * (allow_split ? 4 : 1) < g_target_wgs) nt /= 2;
+  }
+  if (need_even_nt && nt < 2) nt = 2;
+  if (p.mt == 9 && nt > 2) nt = 2;  // accumulators of 9 x 4 tiles exceed the register file
+  p.nt = nt;
+  int nblocks = (ntiles + 4 * nt - 1) / (4 * nt);
+  int splits = 1;
+  if (allow_split) {
+    if (g_force_splits) {
+      splits = g_force_splits;
+    } else {
+      splits = (g_target_wgs + nblocks - 1) / nblocks;
+    }
+    int max_splits = nchunks / 4;  // at least four 128-wide chunks per split
+    if (max_splits < 1) max_splits = 1;
+    if (splits > max_splits) splits = max_splits;
+    if (splits > 16) splits = 16;
+    if (splits < 1) splits = 1;
+    // drop empty trailing splits
+    int cps = (nchunks + splits - 1) / splits;
+    splits = (nchunks + cps - 1) / cps;
+  }
+  p.splits = splits;
+  return p;
+}
+
+struct Workspace {
+  float* x;          // [M, d] residual stream
+  void* xn;          // [M, d] normalised activations (model dtype)
+  float* partial;    // split-K partial sums
+  void* q;           // [M, Hq*hd]
+  void* o;           // [M, Hq*hd]
+  void* a;           // [M, F]
+  float* rope;       // [M, hd/2, 2]
+  float* attn;       // attention split partials
+  float* lm_partial; // LM-head statistics partials
+  size_t bytes;
+};
+
+struct Plans {
+  GemmPlan qkv, wo, gateup, down, lm;
+  AttnPlan attn;
+  int lm_parts;
+};
+
+size_t lmhead_partial_floats(int M, int V, int dtype, const GemmPlan& lm) {
+  int parts = dtype == FLY_BF16 ? gemm_bf16_lmhead_parts(V, lm) : gemm_f32_lmhead_parts(V);
+  return (size_t)M * parts * 4;
+}
+
+fly_status check_desc(const fly_model_desc* desc) {
+  if (!desc) return FLY_ERR_NULL_POINTER;
+  if (desc->dtype != FLY_F32 && desc->dtype != FLY_BF16) return FLY_ERR_DTYPE;
+  if (desc->n_layers < 0 || desc->d < 16 || desc->n_q_heads < 1 || desc->n_kv_heads < 1 ||
+      desc->ffn < 16 || desc->vocab < 16)
+    return FLY_ERR_BAD_SHAPE;
+  if (desc->n_q_heads % desc->n_kv_heads != 0) return FLY_ERR_BAD_SHAPE;
+  if (desc->dtype == FLY_BF16) {
+    if (desc->head_dim != 128) return FLY_ERR_HEAD_DIM;
+    if (desc->d % 32 != 0 || desc->ffn % 32 != 0 || desc->vocab % 16 != 0) return FLY_ERR_BAD_SHAPE;
+  } else {
+    if (desc->head_dim != 64 && desc->head_dim != 128) return FLY_ERR_HEAD_DIM;
+    if (desc->d % 16 != 0 || desc->ffn % 16 != 0 || desc->vocab % 16 != 0) return FLY_ERR_BAD_SHAPE;
+  }
+  return FLY_OK;
+}
+
+fly_status check_block(int B, int K) {
+  if (B < 1 || B > 4096) return FLY_ERR_BAD_SHAPE;
+  if (K < 1 || K > 63) return FLY_ERR_K_RANGE;
+  return FLY_OK;
+}
+
+fly_status make_plans(const fly_model_desc* desc, int B, int K, int max_kv_len, Plans* pl) {
+  const int M = B * (K + 1);
+  const int qkvN = (desc->n_q_heads + 2 * desc->n_kv_heads) * desc->head_dim;
+  const int qdim = desc->n_q_heads * desc->head_dim;
+  if (desc->dtype == FLY_BF16) {
+    pl->qkv = plan_gemm(M, qkvN, desc->d, true, false);
+    pl->wo = plan_gemm(M, desc->d, qdim, true, false);
+    pl->gateup = plan_gemm(M, 2 * desc->ffn, desc->d, false, true);
+    pl->down = plan_gemm(M, desc->d, desc->ffn, true, false);
+    pl->lm = plan_gemm(M, desc->vocab, desc->d, false, false);
+    pl->attn = plan_attention(B, K, desc->n_q_heads, desc->n_kv_heads, max_kv_len + K + 1);
+    if (pl->attn.nwaves > 8) return FLY_ERR_BAD_SHAPE;  // more than 384 query rows per KV head
+  } else {
+    GemmPlan one{1, 1, 1, 1};
+    pl->qkv = pl->wo = pl->gateup = pl->down = pl->lm = one;
+    pl->attn = AttnPlan{1, 1, 1, 64};
+  }
+  pl->lm_parts = desc->dtype == FLY_BF16 ? gemm_bf16_lmhead_parts(desc->vocab, pl->lm)
+                                         : gemm_f32_lmhead_parts(desc->vocab);
+  return FLY_OK;
+}
+
+// Carve the workspace; with base == NULL only the size is computed.
+void carve(const fly_model_desc* desc, int B, int K, const Plans& pl, void* base, Workspace* ws) {
+  const size_t M = (size_t)B * (K + 1);
+  const size_t es = elem_size(desc->dtype);
+  const size_t qkvN = (size_t)(desc->n_q_heads + 2 * desc->n_kv_heads) * desc->head_dim;
+  const size_t qdim = (size_t)desc->n_q_heads * desc->head_dim;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    void* p = base ? (void*)((char*)base + off) : nullptr;
+    off += round_up(bytes, 256);
+    return p;
+  };
+  ws->x = (float*)take(M * desc->d * 4);
+  ws->xn = take(M * desc->d * es);
+  size_t pf = (size_t)pl.qkv.splits * M * qkvN;
+  size_t pf2 = (size_t)pl.wo.splits * M * desc->d;
+  size_t pf3 = (size_t)pl.down.splits * M * desc->d;
+  if (pf2 > pf) pf = pf2;
+  if (pf3 > pf) pf = pf3;
+  ws->partial = (float*)take(pf * 4);
+  ws->q = take(M * qdim * es);
+  ws->o = take(M * qdim * es);
+  ws->a = take(M * (size_t)desc->ffn * es);
+  ws->rope = (float*)take(M * desc->head_dim * 4);
+  size_t af = desc->dtype == FLY_BF16 ? attention_workspace_floats(B, K, desc->n_q_heads, desc->n_kv_heads,
+                                                                   desc->head_dim, pl.attn)
+                                      : 0;
+  ws->attn = (float*)take(af * 4);
+  ws->lm_partial = (float*)take((size_t)M * pl.lm_parts * 16);
+  ws->bytes = off;
+}
+
+#define HIP_TRY(expr)                          \
+  do {                                         \
+    hipError_t _e = (expr);                    \
+    if (_e != hipSuccess) return FLY_ERR_LAUNCH; \
+  } while (0)
+
+fly_status check_kv(const fly_model_desc* desc, const fly_kv_cache* kv, int K, int layer_begin,
+                    int layer_end) {
+  if (!kv || !kv->kv_len) return FLY_ERR_NULL_POINTER;
+  if (layer_end > layer_begin && (!kv->k_layers || !kv->v_layers)) return FLY_ERR_NULL_POINTER;
+  if (kv->capacity < 64 || kv->capacity % 64 != 0) return FLY_ERR_BAD_SHAPE;
+  if (kv->max_kv_len < 0) return FLY_ERR_BAD_SHAPE;
+  if ((int64_t)kv->max_kv_len + K + 1 > kv->capacity) return FLY_ERR_KV_CAPACITY;
+  for (int l = layer_begin; l < layer_end; ++l) {
+    if (!kv->k_layers[l] || !kv->v_layers[l]) return FLY_ERR_NULL_POINTER;
+    if (!aligned16(kv->k_layers[l]) || !aligned16(kv->v_layers[l])) return FLY_ERR_ALIGNMENT;
+  }
+  return FLY_OK;
+}
+
+fly_status check_weights(const fly_model_desc* desc, const fly_weights* w, int layer_begin,
+                         int layer_end, bool need_head) {
+  if (!w) return FLY_ERR_NULL_POINTER;
+  if (layer_end > layer_begin && !w->layers) return FLY_ERR_NULL_POINTER;
+  for (int l = layer_begin; l < layer_end; ++l) {
+    const fly_layer_weights& lw = w->layers[l];
+    const void* ps[6] = {lw.w_qkv, lw.w_o, lw.w_gateup, lw.w_down, lw.g_attn, lw.g_ffn};
+    for (int i = 0; i < 6; ++i) {
+      if (!ps[i]) return FLY_ERR_NULL_POINTER;
+      if (!aligned16(ps[i])) return FLY_ERR_ALIGNMENT;
+    }
+  }
+  if (layer_end > layer_begin) {
+    // the norm after the last requested layer uses the next layer's gain (or g_final)
+    const void* next_gain = layer_end < desc->n_layers ? w->layers[layer_end].g_attn : w->g_final;
+    if (!next_gain) return FLY_ERR_NULL_POINTER;
+    if (!aligned16(next_gain)) return FLY_ERR_ALIGNMENT;
+  }
+  if (need_head) {
+    if (!w->embed || !w->g_final || !w->w_lm) return FLY_ERR_NULL_POINTER;
+    if (!aligned16(w->embed) || !aligned16(w->g_final) || !aligned16(w->w_lm)) return FLY_ERR_ALIGNMENT;
+  }
+  return FLY_OK;
+}
+
+// One GEMM of the layer in either dtype; bf16 may leave split-K partials.
+fly_status run_gemm(int dtype, const void* X, const void* W, void* out, const float* row_scale, int M,
+                    int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st) {
+  if (dtype == FLY_BF16)
+    HIP_TRY(launch_gemm_bf16((const bf16_t*)X, (const bf16_t*)W, out, row_scale, M, N, Kd, plan, epi, st));
+  else
+    HIP_TRY(launch_gemm_f32((const float*)X, (const float*)W, out, row_scale, M, N, Kd, epi, st));
+  return FLY_OK;
+}
+
+#define FLY_TRY(expr)               \
+  do {                              \
+    fly_status _s = (expr);         \
+    if (_s != FLY_OK) return _s;    \
+  } while (0)
+
+// Layers [l0, l1) on the residual stream ws.x; ws.xn must hold
+// rmsnorm(x) * g_attn[l0] on entry and holds rmsnorm(x) * next_gain on exit
+// (next_gain = g_attn of layer l1, or g_final after the last layer).
+fly_status run_layers(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                      const Workspace& ws, const Plans& pl, int l0, int l1, int B, int K,
+                      hipStream_t st) {
+  const int M = B * (K + 1), d = desc->d, dt = desc->dtype;
+  const int Hq = desc->n_q_heads, Hkv = desc->n_kv_heads, hd = desc->head_dim;
+  const int qkvN = (Hq + 2 * Hkv) * hd, qdim = Hq * hd;
+  for (int l = l0; l < l1; ++l) {
+    const fly_layer_weights& lw = w->layers[l];
+    // q, k, v projection -> rotate -> append to the cache
+    FLY_TRY(run_gemm(dt, ws.xn, lw.w_qkv, ws.partial, nullptr, M, qkvN, d, pl.qkv, EPI_PARTIAL, st));
+    HIP_TRY(launch_qkv_epilogue(ws.partial, pl.qkv.splits, ws.rope, ws.q, kv->k_layers[l],
+                                kv->v_layers[l], kv->kv_len, dt, B, K, Hq, Hkv, hd, kv->capacity, st));
+    // attention over prefix + new rows
+    if (dt == FLY_BF16)
+      HIP_TRY(launch_attention_bf16((const bf16_t*)ws.q, (const bf16_t*)kv->k_layers[l],
+                                    (const bf16_t*)kv->v_layers[l], kv->kv_len, (bf16_t*)ws.o, ws.attn,
+                                    B, K, Hq, Hkv, hd, kv->capacity, pl.attn, st));
+    else
+      HIP_TRY(launch_attention_f32((const float*)ws.q, (const float*)kv->k_layers[l],
+                                   (const float*)kv->v_layers[l], kv->kv_len, (float*)ws.o, B, K, Hq,
+                                   Hkv, hd, kv->capacity, st));
+    // output projection + residual, then the FFN norm
+    FLY_TRY(run_gemm(dt, ws.o, lw.w_o, ws.partial, nullptr, M, d, qdim, pl.wo, EPI_PARTIAL, st));
+    HIP_TRY(launch_reduce_residual_norm(ws.x, ws.partial, pl.wo.splits, lw.g_ffn, ws.xn, dt, M, d,
+                                        desc->rms_eps, st));
+    // SwiGLU FFN + residual, then the next norm
+    FLY_TRY(run_gemm(dt, ws.xn, lw.w_gateup, ws.a, nullptr, M, 2 * desc->ffn, d, pl.gateup, EPI_SWIGLU, st));
+    FLY_TRY(run_gemm(dt, ws.a, lw.w_down, ws.partial, nullptr, M, d, desc->ffn, pl.down, EPI_PARTIAL, st));
+    const void* next_gain = (l + 1 < desc->n_layers) ? w->layers[l + 1].g_attn : w->g_final;
+    HIP_TRY(launch_reduce_residual_norm(ws.x, ws.partial, pl.down.splits, next_gain, ws.xn, dt, M, d,
+                                        desc->rms_eps, st));
+  }
+  return FLY_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* fly_strerror(fly_status s) {
+  switch (s) {
+    case FLY_OK: return "ok";
+    case FLY_ERR_NULL_POINTER: return "a required pointer is NULL";
+    case FLY_ERR_BAD_SHAPE: return "a size is out of range or not a multiple of the tile granularity";
+    case FLY_ERR_K_RANGE: return "K must be in [1, 63]";
+    case FLY_ERR_WINDOW: return "W must be >= 0";
+    case FLY_ERR_THETA: return "theta is NaN";
+    case FLY_ERR_DTYPE: return "unknown dtype";
+    case FLY_ERR_HEAD_DIM: return "unsupported head_dim";
+    case FLY_ERR_ALIGNMENT: return "a device pointer is not 16-byte aligned";
+    case FLY_ERR_WORKSPACE: return "workspace missing or too small";
+    case FLY_ERR_KV_CAPACITY: return "max_kv_len + K + 1 exceeds the KV cache capacity";
+    case FLY_ERR_LAUNCH: return "the HIP runtime refused a launch";
+  }
+  return "unknown status";
+}
+
+// Tuning knobs for experiments: "gemm_nt" (1, 2, 4; 0 = automatic),
+// "gemm_splits" (0 = automatic), "target_wgs" (workgroups a launch aims for).
+fly_status fly_set_tuning(const char* key, int32_t value) {
+  if (!key) return FLY_ERR_NULL_POINTER;
+  if (!strcmp(key, "gemm_nt")) {
+    if (value != 0 && value != 1 && value != 2 && value != 4) return FLY_ERR_BAD_SHAPE;
+    g_force_nt = value;
+  } else if (!strcmp(key, "gemm_splits")) {
+    if (value < 0 || value > 16) return FLY_ERR_BAD_SHAPE;
+    g_force_splits = value;
+  } else if (!strcmp(key, "target_wgs")) {
+    if (value < 1) return FLY_ERR_BAD_SHAPE;
+    g_target_wgs = value;
+  } else {
+    return FLY_ERR_BAD_SHAPE;
+  }
+  return FLY_OK;
+}
+
+fly_status fly_packed_weight_bytes(int64_t k_in, int64_t n_dst, int32_t dtype, size_t* bytes) {
+  if (!bytes) return FLY_ERR_NULL_POINTER;
+  if (dtype != FLY_F32 && dtype != FLY_BF16) return FLY_ERR_DTYPE;
+  if (k_in < 1 || n_dst < 16 || n_dst % 16 != 0) return FLY_ERR_BAD_SHAPE;
+  if (dtype == FLY_BF16 && k_in % 32 != 0) return FLY_ERR_BAD_SHAPE;
+  *bytes = (size_t)k_in * (size_t)n_dst * elem_size(dtype);
+  return FLY_OK;
+}
+
+fly_status fly_pack_weight(const void* src, int64_t k_in, int64_t n_src, int32_t dtype, void* dst,
+                           int64_t n_dst, int64_t tile_offset, int64_t tile_stride,
+                           fly_stream stream) {
+  if (!src || !dst) return FLY_ERR_NULL_POINTER;
+  if (dtype != FLY_F32 && dtype != FLY_BF16) return FLY_ERR_DTYPE;
+  if (k_in < 1 || n_src < 16 || n_src % 16 != 0 || n_dst < 16 || n_dst % 16 != 0) return FLY_ERR_BAD_SHAPE;
+  if (dtype == FLY_BF16 && k_in % 32 != 0) return FLY_ERR_BAD_SHAPE;
+  if (tile_offset < 0 || tile_stride < 1) return FLY_ERR_BAD_SHAPE;
+  // the last source tile must land inside the destination
+  if (tile_offset + (n_src / 16 - 1) * tile_stride >= n_dst / 16) return FLY_ERR_BAD_SHAPE;
+  if (!aligned16(src) || !aligned16(dst)) return FLY_ERR_ALIGNMENT;
+  HIP_TRY(launch_pack_weight(src, k_in, n_src, dtype, dst, n_dst, tile_offset, tile_stride,
+                             (hipStream_t)stream));
+  return FLY_OK;
+}
+
+fly_status fly_workspace_bytes(const fly_model_desc* desc, int32_t B, int32_t K, int32_t max_kv_len,
+                               size_t* bytes) {
+  if (!bytes) return FLY_ERR_NULL_POINTER;
+  FLY_TRY(check_desc(desc));
+  FLY_TRY(check_block(B, K));
+  if (max_kv_len < 0) return FLY_ERR_BAD_SHAPE;
+  Plans pl;
+  FLY_TRY(make_plans(desc, B, K, max_kv_len, &pl));
+  Workspace ws;
+  carve(desc, B, K, pl, nullptr, &ws);
+  *bytes = ws.bytes;
+  return FLY_OK;
+}
+
+fly_status fly_lmhead_workspace_bytes(int32_t M, int32_t d, int32_t V, int32_t dtype, size_t* bytes) {
+  if (!bytes) return FLY_ERR_NULL_POINTER;
+  if (dtype != FLY_F32 && dtype != FLY_BF16) return FLY_ERR_DTYPE;
+  if (M < 1 || d < 16 || V < 16 || V % 16 != 0) return FLY_ERR_BAD_SHAPE;
+  if (dtype == FLY_BF16 && d % 32 != 0) return FLY_ERR_BAD_SHAPE;
+  GemmPlan lm = dtype == FLY_BF16 ? plan_gemm(M, V, d, false, false) : GemmPlan{1, 1, 1, 1};
+  *bytes = round_up(lmhead_partial_floats(M, V, dtype, lm) * 4, 256);
+  return FLY_OK;
+}
+
+fly_status fly_lmhead_entropy_argmax(const void* hidden, const void* w_lm, const float* row_scale,
+                                     int32_t M, int32_t d, int32_t V, int32_t dtype, int32_t* argmax,
+                                     float* p_top1, float* h_norm, float* lse, void* workspace,
+                                     size_t workspace_bytes, fly_stream stream) {
+  if (!hidden || !w_lm || !argmax || !p_top1 || !h_norm) return FLY_ERR_NULL_POINTER;
+  size_t need = 0;
+  FLY_TRY(fly_lmhead_workspace_bytes(M, d, V, dtype, &need));
+  if (!workspace || workspace_bytes < need) return FLY_ERR_WORKSPACE;
+  if (!aligned16(hidden) || !aligned16(w_lm) || !aligned16(workspace)) return FLY_ERR_ALIGNMENT;
+  hipStream_t st = (hipStream_t)stream;
+  GemmPlan lm = dtype == FLY_BF16 ? plan_gemm(M, V, d, false, false) : GemmPlan{1, 1, 1, 1};
+  int parts = dtype == FLY_BF16 ? gemm_bf16_lmhead_parts(V, lm) : gemm_f32_lmhead_parts(V);
+  FLY_TRY(run_gemm(dtype, hidden, w_lm, workspace, row_scale, M, V, d, lm, EPI_LMHEAD, st));
+  HIP_TRY(launch_lmhead_combine((const float*)workspace, parts, M, V, argmax, p_top1, h_norm, lse, st));
+  return FLY_OK;
+}
+
+fly_status fly_accept(const int32_t* draft, const int32_t* tgt_argmax, const float* h_norm, int32_t B,
+                      int32_t K, float theta, int32_t W, int32_t* accept_len, int32_t* next_token,
+                      int32_t* n_loose, fly_stream stream) {
+  if (!draft || !tgt_argmax || !h_norm || !accept_len || !next_token) return FLY_ERR_NULL_POINTER;
+  FLY_TRY(check_block(B, K));
+  if (W < 0) return FLY_ERR_WINDOW;
+  if (theta != theta) return FLY_ERR_THETA;
+  HIP_TRY(launch_accept(draft, K, tgt_argmax, h_norm, nullptr, B, K, theta, W, accept_len, next_token,
+                        n_loose, nullptr, (hipStream_t)stream));
+  return FLY_OK;
+}
+
+fly_status fly_decoder_layers(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                              float* x, int32_t layer_begin, int32_t layer_end, int32_t B, int32_t K,
+                              void* workspace, size_t workspace_bytes, fly_stream stream) {
+  FLY_TRY(check_desc(desc));
+  FLY_TRY(check_block(B, K));
+  if (!x) return FLY_ERR_NULL_POINTER;
+  if (layer_begin < 0 || layer_end > desc->n_layers || layer_begin > layer_end) return FLY_ERR_BAD_SHAPE;
+  FLY_TRY(check_weights(desc, w, layer_begin, layer_end, false));
+  FLY_TRY(check_kv(desc, kv, K, layer_begin, layer_end));
+  Plans pl;
+  FLY_TRY(make_plans(desc, B, K, kv->max_kv_len, &pl));
+  Workspace ws;
+  carve(desc, B, K, pl, nullptr, &ws);
+  if (!workspace || workspace_bytes < ws.bytes) return FLY_ERR_WORKSPACE;
+  if (!aligned16(workspace) || !aligned16(x)) return FLY_ERR_ALIGNMENT;
+  carve(desc, B, K, pl, workspace, &ws);
+  if (layer_begin == layer_end) return FLY_OK;
+  hipStream_t st = (hipStream_t)stream;
+  const int M = B * (K + 1);
+  HIP_TRY(hipMemcpyAsync(ws.x, x, (size_t)M * desc->d * 4, hipMemcpyDeviceToDevice, st));
+  HIP_TRY(launch_rope_table(kv->kv_len, ws.rope, B, K, desc->head_dim, desc->rope_theta, st));
+  HIP_TRY(launch_reduce_residual_norm(ws.x, nullptr, 0, w->layers[layer_begin].g_attn, ws.xn,
+                                      desc->dtype, M, desc->d, desc->rms_eps, st));
+  FLY_TRY(run_layers(desc, w, kv, ws, pl, layer_begin, layer_end, B, K, st));
+  HIP_TRY(hipMemcpyAsync(x, ws.x, (size_t)M * desc->d * 4, hipMemcpyDeviceToDevice, st));
+  return FLY_OK;
+}
+
+fly_status fly_attention(const fly_model_desc* desc, const fly_kv_cache* kv, int32_t layer, const void* q,
+                         void* o, int32_t B, int32_t K, void* workspace, size_t workspace_bytes,
+                         fly_stream stream) {
+  FLY_TRY(check_desc(desc));
+  FLY_TRY(check_block(B, K));
+  if (!q || !o) return FLY_ERR_NULL_POINTER;
+  if (layer < 0 || layer >= desc->n_layers) return FLY_ERR_BAD_SHAPE;
+  FLY_TRY(check_kv(desc, kv, K, layer, layer + 1));
+  Plans pl;
+  FLY_TRY(make_plans(desc, B, K, kv->max_kv_len, &pl));
+  Workspace ws;
+  carve(desc, B, K, pl, nullptr, &ws);
+  if (!workspace || workspace_bytes < ws.bytes) return FLY_ERR_WORKSPACE;
+  if (!aligned16(workspace) || !aligned16(q) || !aligned16(o)) return FLY_ERR_ALIGNMENT;
+  carve(desc, B, K, pl, workspace, &ws);
+  hipStream_t st = (hipStream_t)stream;
+  if (desc->dtype == FLY_BF16)
+    HIP_TRY(launch_attention_bf16((const bf16_t*)q, (const bf16_t*)kv->k_layers[layer],
+                                  (const bf16_t*)kv->v_layers[layer], kv->kv_len, (bf16_t*)o, ws.attn, B,
+                                  K, desc->n_q_heads, desc->n_kv_heads, desc->head_dim, kv->capacity,
+                                  pl.attn, st));
+  else
+    HIP_TRY(launch_attention_f32((const float*)q, (const float*)kv->k_layers[layer],
+                                 (const float*)kv->v_layers[layer], kv->kv_len, (float*)o, B, K,
+                                 desc->n_q_heads, desc->n_kv_heads, desc->head_dim, kv->capacity, st));
+  return FLY_OK;
+}
+
+fly_status fly_verify_block(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                            const int32_t* tokens, const float* row_scale, int32_t B, int32_t K,
+                            float theta, int32_t W, const fly_verify_out* out, void* workspace,
+                            size_t workspace_bytes, fly_stream stream) {
+  FLY_TRY(check_desc(desc));
+  FLY_TRY(check_block(B, K));
+  if (W < 0) return FLY_ERR_WINDOW;
+  if (theta != theta) return FLY_ERR_THETA;
+  if (!tokens || !out) return FLY_ERR_NULL_POINTER;
+  if (!out->accept_len || !out->next_token || !out->kv_len_out || !out->argmax || !out->h_norm ||
+      !out->p_top1)
+    return FLY_ERR_NULL_POINTER;
+  FLY_TRY(check_weights(desc, w, 0, desc->n_layers, true));
+  FLY_TRY(check_kv(desc, kv, K, 0, desc->n_layers));
+  Plans pl;
+  FLY_TRY(make_plans(desc, B, K, kv->max_kv_len, &pl));
+  Workspace ws;
+  carve(desc, B, K, pl, nullptr, &ws);
+  if (!workspace || workspace_bytes < ws.bytes) return FLY_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return FLY_ERR_ALIGNMENT;
+  carve(desc, B, K, pl, workspace, &ws);
+
+  hipStream_t st = (hipStream_t)stream;
+  const int M = B * (K + 1), d = desc->d, dt = desc->dtype;
+  HIP_TRY(launch_rope_table(kv->kv_len, ws.rope, B, K, desc->head_dim, desc->rope_theta, st));
+  HIP_TRY(launch_embed(tokens, w->embed, dt, ws.x, M, d, desc->vocab, st));
+  const void* first_gain = desc->n_layers > 0 ? w->layers[0].g_attn : w->g_final;
+  HIP_TRY(launch_reduce_residual_norm(ws.x, nullptr, 0, first_gain, ws.xn, dt, M, d, desc->rms_eps, st));
+  FLY_TRY(run_layers(desc, w, kv, ws, pl, 0, desc->n_layers, B, K, st));
+  if (out->hidden_out)
+    HIP_TRY(hipMemcpyAsync(out->hidden_out, ws.x, (size_t)M * d * 4, hipMemcpyDeviceToDevice, st));
+  // LM head with fused statistics: logits stay in registers
+  FLY_TRY(run_gemm(dt, ws.xn, w->w_lm, ws.lm_partial, row_scale, M, desc->vocab, d, pl.lm, EPI_LMHEAD, st));
+  HIP_TRY(launch_lmhead_combine(ws.lm_partial, pl.lm_parts, M, desc->vocab, out->argmax, out->p_top1,
+                                out->h_norm, out->lse, st));
+  // acceptance rule on (draft, argmax, h)
+  HIP_TRY(launch_accept(tokens + 1, K + 1, out->argmax, out->h_norm, kv->kv_len, B, K, theta, W,
+                        out->accept_len, out->next_token, out->n_loose, out->kv_len_out, st));
+  return FLY_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,137 @@
+// Shared declarations of the HIP sources (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/fly.h"
+
+typedef uint16_t bf16_t;  // raw bf16 bits
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+#define FLY_WAVE 64
+
+// fp32 -> bf16, round to nearest even (NaN not handled: inputs are finite).
+__device__ __forceinline__ bf16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) {
+  return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
+
+template <typename T> struct Act;
+template <> struct Act<float> {
+  static __device__ __forceinline__ float ld(const float* p) { return *p; }
+  static __device__ __forceinline__ void st(float* p, float v) { *p = v; }
+};
+template <> struct Act<bf16_t> {
+  static __device__ __forceinline__ float ld(const bf16_t* p) { return bf2f(*p); }
+  static __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f2bf(v); }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, FLY_WAVE);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, FLY_WAVE));
+  return v;
+}
+
+// Running softmax statistics of a set of logits: maximum m, s = sum e^(l-m),
+// t = sum (l-m) e^(l-m), and the lowest index attaining m.  From them
+// lse = m + ln s and the entropy H = ln s - t/s (Eq. 5 rearranged).
+struct RowStat {
+  float m, s, t;
+  int32_t idx;
+};
+__device__ __forceinline__ RowStat stat_empty() { return RowStat{-INFINITY, 0.f, 0.f, 0x7fffffff}; }
+__device__ __forceinline__ RowStat stat_merge(const RowStat& a, const RowStat& b) {
+  RowStat r;
+  if (b.s == 0.f) return a;
+  if (a.s == 0.f) return b;
+  r.m = fmaxf(a.m, b.m);
+  float da = a.m - r.m, db = b.m - r.m;  // <= 0
+  float ea = __expf(da), eb = __expf(db);
+  r.s = a.s * ea + b.s * eb;
+  r.t = (a.t + da * a.s) * ea + (b.t + db * b.s) * eb;
+  r.idx = (a.m > b.m) ? a.idx : (b.m > a.m) ? b.idx : min(a.idx, b.idx);
+  return r;
+}
+__device__ __forceinline__ RowStat stat_shfl_xor(const RowStat& a, int o) {
+  RowStat r;
+  r.m = __shfl_xor(a.m, o, FLY_WAVE);
+  r.s = __shfl_xor(a.s, o, FLY_WAVE);
+  r.t = __shfl_xor(a.t, o, FLY_WAVE);
+  r.idx = __shfl_xor(a.idx, o, FLY_WAVE);
+  return r;
+}
+
+// ---- host-side launchers (defined in the kernel sources) -------------------
+struct GemmPlan {
+  int mt;      // 16-row tiles of activations held per workgroup (1,2,3,5,9)
+  int nt;      // 16-column weight tiles per wave (1,2,4)
+  int splits;  // split-K factor (partial results go to the workspace)
+  int mblocks; // row blocks (activations beyond 144 rows re-stream the weights)
+};
+
+enum GemmEpilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_LMHEAD = 2 };
+
+hipError_t launch_pack_weight(const void* src, int64_t k_in, int64_t n_src, int dtype, void* dst,
+                              int64_t n_dst, int64_t tile_offset, int64_t tile_stride,
+                              hipStream_t st);
+
+// bf16 weight-streaming GEMM: out = X[M,Kd] * W[Kd,N] (W packed).
+//   EPI_PARTIAL: out = float partial[splits][M][N]
+//   EPI_SWIGLU : out = bf16 a[M][N/2], a = silu(gate)*up (splits must be 1)
+//   EPI_LMHEAD : out = RowStat-like float4 partial[M][nparts] (splits must be 1),
+//                logits multiplied by row_scale[m] first
+hipError_t launch_gemm_bf16(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale,
+                            int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st);
+int gemm_bf16_lmhead_parts(int N, const GemmPlan& plan);
+
+// fp32 GEMM (weights row-major [Kd,N]) with the same epilogues; no split-K.
+hipError_t launch_gemm_f32(const float* X, const float* W, void* out, const float* row_scale, int M,
+                           int N, int Kd, int epi, hipStream_t st);
+int gemm_f32_lmhead_parts(int N);
+
+hipError_t launch_embed(const int32_t* tokens, const void* embed, int dtype, float* x, int M, int d,
+                        int vocab, hipStream_t st);
+// x[m] += sum_s partial[s][m] (partial may be NULL with splits = 0), then
+// xn[m] = rmsnorm(x[m]) * gain in the activation dtype (xn may be NULL).
+hipError_t launch_reduce_residual_norm(float* x, const float* partial, int splits, const void* gain,
+                                       void* xn, int dtype, int M, int d, float eps, hipStream_t st);
+hipError_t launch_rope_table(const int32_t* kv_len, float* table, int B, int K, int hd, float theta,
+                             hipStream_t st);
+// Sum split-K partials of the fused q/k/v projection, rotate q and k, write q
+// (activation dtype) and append k, v to the cache.
+hipError_t launch_qkv_epilogue(const float* partial, int splits, const float* rope, void* q,
+                               void* kcache, void* vcache, const int32_t* kv_len, int dtype, int B,
+                               int K, int Hq, int Hkv, int hd, int capacity, hipStream_t st);
+hipError_t launch_lmhead_combine(const float* partial, int nparts, int M, int V, int32_t* argmax,
+                                 float* p_top1, float* h_norm, float* lse, hipStream_t st);
+hipError_t launch_accept(const int32_t* draft, int draft_stride, const int32_t* tgt,
+                         const float* h_norm, const int32_t* kv_len, int B, int K, float theta,
+                         int W, int32_t* accept_len, int32_t* next_token, int32_t* n_loose,
+                         int32_t* kv_len_out, hipStream_t st);
+
+struct AttnPlan {
+  int nsplit;      // KV splits per (sequence, kv head)
+  int qtw;         // 16-row query tiles per wave (1..3)
+  int nwaves;      // waves per workgroup
+  int chunk_keys;  // keys per split (multiple of 64)
+};
+AttnPlan plan_attention(int B, int K, int Hq, int Hkv, int max_total_len);
+size_t attention_workspace_floats(int B, int K, int Hq, int Hkv, int hd, const AttnPlan& p);
+hipError_t launch_attention_bf16(const bf16_t* q, const bf16_t* kcache, const bf16_t* vcache,
+                                 const int32_t* kv_len, bf16_t* o, float* ws, int B, int K, int Hq,
+                                 int Hkv, int hd, int capacity, const AttnPlan& p, hipStream_t st);
+hipError_t launch_attention_f32(const float* q, const float* kcache, const float* vcache,
+                                const int32_t* kv_len, float* o, int B, int K, int Hq, int Hkv,
+                                int hd, int capacity, hipStream_t st);

@@ -1,0 +1,459 @@
+// Weight packing and the weight-streaming GEMMs of the verification forward
+// (layer projections and the LM head; paper Sec. 2.1, Algorithm 1 step 2).
+//
+// The block of K+1 draft positions gives M = B*(K+1) activation rows, a few
+// dozen, against weight matrices of 10^8..10^9 entries, so every GEMM here is
+// bound by reading the weights once from HBM.  The bf16 kernel therefore
+// streams packed weight tiles straight from global memory into matrix-core
+// operand registers (each wave-level load is one contiguous KiB), keeps the
+// small activation block in LDS in operand order, and computes
+// out^T[n, m] = sum_k W[k, n] X[m, k] with v_mfma_f32_16x16x32_bf16 so that the
+// weight tile is the A operand and the activations are the B operand.
+#include "fly_common.h"
+
+// ---------------------------------------------------------------------------
+// Packing
+// ---------------------------------------------------------------------------
+// bf16 packed layout: tile (tn, tk) covers columns 16tn..16tn+15 and rows
+// 32tk..32tk+31 of W[k_in, n]; it occupies 64 lanes x 8 values, lane l holding
+// W[32tk + 8(l/16) + i][16tn + l%16], i = 0..7.  Tiles of one column strip are
+// contiguous along tk.
+__global__ void pack_bf16_kernel(const bf16_t* __restrict__ src, bf16_t* __restrict__ dst,
+                                 int64_t k_in, int64_t n_src, int64_t tile_offset,
+                                 int64_t tile_stride) {
+  int64_t ktiles = k_in / 32;
+  int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;  // one (tile, lane) each
+  int64_t total = (n_src / 16) * ktiles * 64;
+  if (gid >= total) return;
+  int lane = (int)(gid % 64);
+  int64_t tile = gid / 64;
+  int64_t tk = tile % ktiles;
+  int64_t tj = tile / ktiles;  // source column tile
+  int64_t tn = tile_offset + tj * tile_stride;
+  int64_t col = tj * 16 + (lane & 15);
+  int64_t row0 = tk * 32 + 8 * (lane >> 4);
+  bf16_t v[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = src[(row0 + i) * n_src + col];
+  bf16_t* d = dst + ((tn * ktiles + tk) * 64 + lane) * 8;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) d[i] = v[i];
+}
+
+__global__ void pack_f32_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t k_in,
+                                int64_t n_src, int64_t n_dst, int64_t tile_offset,
+                                int64_t tile_stride) {
+  int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= k_in * n_src) return;
+  int64_t k = gid / n_src, c = gid % n_src;
+  int64_t tn = tile_offset + (c / 16) * tile_stride;
+  dst[k * n_dst + tn * 16 + (c & 15)] = src[gid];
+}
+
+hipError_t launch_pack_weight(const void* src, int64_t k_in, int64_t n_src, int dtype, void* dst,
+                              int64_t n_dst, int64_t tile_offset, int64_t tile_stride,
+                              hipStream_t st) {
+  if (dtype == FLY_BF16) {
+    int64_t total = (n_src / 16) * (k_in / 32) * 64;
+    int64_t blocks = (total + 255) / 256;
+    hipLaunchKernelGGL(pack_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                       (const bf16_t*)src, (bf16_t*)dst, k_in, n_src, tile_offset, tile_stride);
+  } else {
+    int64_t total = k_in * n_src;
+    int64_t blocks = (total + 255) / 256;
+    hipLaunchKernelGGL(pack_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, st, (const float*)src,
+                       (float*)dst, k_in, n_src, n_dst, tile_offset, tile_stride);
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// bf16 weight-streaming GEMM
+// ---------------------------------------------------------------------------
+#define GEMM_KS 4  // 32-wide k-steps per LDS stage (128 k)
+
+__device__ __forceinline__ float silu_f(float x) { return x / (1.f + __expf(-x)); }
+
+template <int MT, int NT>
+struct GemmRegs {
+  f32x4 acc[NT][MT];
+};
+
+// Issue the global loads of one k-chunk: NT x GEMM_KS weight tiles for this wave.
+template <int NT>
+__device__ __forceinline__ void load_weight_chunk(u32x4 (&a)[NT][GEMM_KS], const u32x4* wbase,
+                                                  const bool (&tile_ok)[NT], int64_t strip_stride,
+                                                  int ks0, int ks_end, int lane) {
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+#pragma unroll
+    for (int s = 0; s < GEMM_KS; ++s) {
+      if (tile_ok[j] && ks0 + s < ks_end) {
+        a[j][s] = __builtin_nontemporal_load(wbase + j * strip_stride + (int64_t)(ks0 + s) * 64 + lane);
+      } else {
+        a[j][s] = u32x4{0u, 0u, 0u, 0u};
+      }
+    }
+  }
+}
+
+template <int MT, int NT, int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(
+    const bf16_t* __restrict__ X, const u32x4* __restrict__ Wp, void* __restrict__ out,
+    const float* __restrict__ row_scale, int M, int N, int Kd, int chunks_per_split) {
+  // LDS: two stages of the activation block in operand order
+  // [stage][kstep][mtile][lane] x 16 bytes.
+  __shared__ u32x4 xs[2][GEMM_KS][MT][64];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int g = lane >> 4, c16 = lane & 15;
+  const int ksteps_total = Kd / 32;
+  const int nchunks_total = (ksteps_total + GEMM_KS - 1) / GEMM_KS;
+  const int chunk_begin = blockIdx.y * chunks_per_split;
+  int chunk_end = chunk_begin + chunks_per_split;
+  if (chunk_end > nchunks_total) chunk_end = nchunks_total;
+  const int ks_end = min(chunk_end * GEMM_KS, ksteps_total);
+  const int mrow0 = blockIdx.z * (MT * 16);
+  const int ntiles = N / 16;
+  const int tn0 = (blockIdx.x * 4 + wave) * NT;
+
+  bool tile_ok[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) tile_ok[j] = (tn0 + j) < ntiles;
+  const int64_t strip_stride = (int64_t)ksteps_total * 64;  // u32x4 units per column strip
+  const u32x4* wbase = Wp + (int64_t)tn0 * strip_stride;
+
+  f32x4 acc[NT][MT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j)
+#pragma unroll
+    for (int t = 0; t < MT; ++t) acc[j][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // Activation fragments this wave stages per chunk: f = wave, wave+4, ... < KS*MT.
+  constexpr int NFRAG = (GEMM_KS * MT + 3) / 4;
+  u32x4 xf[NFRAG];
+  auto load_x = [&](int chunk) {
+#pragma unroll
+    for (int i = 0; i < NFRAG; ++i) {
+      int f = wave + 4 * i;
+      int s = f / MT, t = f % MT;
+      int row = mrow0 + t * 16 + c16;
+      int kstep = chunk * GEMM_KS + s;
+      if (f < GEMM_KS * MT && row < M && kstep < ks_end) {
+        xf[i] = *(const u32x4*)(X + (int64_t)row * Kd + kstep * 32 + 8 * g);
+      } else {
+        xf[i] = u32x4{0u, 0u, 0u, 0u};
+      }
+    }
+  };
+  auto store_x = [&](int stage) {
+#pragma unroll
+    for (int i = 0; i < NFRAG; ++i) {
+      int f = wave + 4 * i;
+      if (f < GEMM_KS * MT) xs[stage][f / MT][f % MT][lane] = xf[i];
+    }
+  };
+
+  u32x4 a0[NT][GEMM_KS], a1[NT][GEMM_KS];
+
+  auto compute = [&](const u32x4 (&a)[NT][GEMM_KS], int stage) {
+#pragma unroll
+    for (int s = 0; s < GEMM_KS; ++s) {
+#pragma unroll
+      for (int t = 0; t < MT; ++t) {
+        u32x4 braw = xs[stage][s][t][lane];
+        bf16x8 b = __builtin_bit_cast(bf16x8, braw);
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          bf16x8 av = __builtin_bit_cast(bf16x8, a[j][s]);
+          acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b, acc[j][t], 0, 0, 0);
+        }
+      }
+    }
+  };
+
+  if (chunk_begin < chunk_end) {
+    load_weight_chunk<NT>(a0, wbase, tile_ok, strip_stride, chunk_begin * GEMM_KS, ks_end, lane);
+    load_x(chunk_begin);
+    store_x(0);
+    __syncthreads();
+    int stage = 0;
+    for (int c = chunk_begin; c < chunk_end; c += 2) {
+      // even half: compute from a0, prefetch into a1
+      if (c + 1 < chunk_end) {
+        load_weight_chunk<NT>(a1, wbase, tile_ok, strip_stride, (c + 1) * GEMM_KS, ks_end, lane);
+        load_x(c + 1);
+      }
+      compute(a0, stage);
+      if (c + 1 < chunk_end) store_x(stage ^ 1);
+      __syncthreads();
+      stage ^= 1;
+      if (c + 1 >= chunk_end) break;
+      // odd half: compute from a1, prefetch into a0
+      if (c + 2 < chunk_end) {
+        load_weight_chunk<NT>(a0, wbase, tile_ok, strip_stride, (c + 2) * GEMM_KS, ks_end, lane);
+        load_x(c + 2);
+      }
+      compute(a1, stage);
+      if (c + 2 < chunk_end) store_x(stage ^ 1);
+      __syncthreads();
+      stage ^= 1;
+    }
+  }
+
+  // ---- epilogues.  Lane holds out^T[n = 16*tile + 4g + r][m = 16t + c16], r = 0..3.
+  if constexpr (EPI == EPI_PARTIAL) {
+    float* o = (float*)out + (int64_t)blockIdx.y * M * N;
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      if (!tile_ok[j]) continue;
+#pragma unroll
+      for (int t = 0; t < MT; ++t) {
+        int m = mrow0 + t * 16 + c16;
+        if (m < M) *(f32x4*)(o + (int64_t)m * N + (tn0 + j) * 16 + 4 * g) = acc[j][t];
+      }
+    }
+  } else if constexpr (EPI == EPI_SWIGLU) {
+    // column tiles alternate gate / up; output column = 16*(tile/2) + 4g + r
+    bf16_t* o = (bf16_t*)out;
+    const int Nh = N / 2;
+#pragma unroll
+    for (int j = 0; j + 1 < NT; j += 2) {
+      if (!tile_ok[j + 1]) continue;
+#pragma unroll
+      for (int t = 0; t < MT; ++t) {
+        int m = mrow0 + t * 16 + c16;
+        if (m < M) {
+          f32x4 gt = acc[j][t], up = acc[j + 1][t];
+          u32x2 pk;
+          pk.x = pack_bf2(silu_f(gt.x) * up.x, silu_f(gt.y) * up.y);
+          pk.y = pack_bf2(silu_f(gt.z) * up.z, silu_f(gt.w) * up.w);
+          *(u32x2*)(o + (int64_t)m * Nh + ((tn0 + j) / 2) * 16 + 4 * g) = pk;
+        }
+      }
+    }
+  } else {  // EPI_LMHEAD: per-wave softmax statistics of this wave's columns
+    f32x4* o = (f32x4*)out;
+    const int nparts = gridDim.x * 4;
+    const int part = blockIdx.x * 4 + wave;
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+      int m = mrow0 + t * 16 + c16;
+      float sc = (row_scale != nullptr && m < M) ? row_scale[m] : 1.f;
+      float v[NT][4];
+      float mx = -INFINITY;
+      int idx = 0x7fffffff;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          v[j][r] = acc[j][t][r] * sc;
+          if (tile_ok[j] && v[j][r] > mx) {
+            mx = v[j][r];
+            idx = (tn0 + j) * 16 + 4 * g + r;
+          }
+        }
+      }
+      RowStat st = stat_empty();
+      if (idx != 0x7fffffff) {
+        st.m = mx;
+        st.idx = idx;
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+          if (!tile_ok[j]) continue;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            float dlt = v[j][r] - mx;
+            float e = __expf(dlt);
+            st.s += e;
+            st.t += dlt * e;
+          }
+        }
+      }
+      st = stat_merge(st, stat_shfl_xor(st, 16));
+      st = stat_merge(st, stat_shfl_xor(st, 32));
+      if (g == 0 && m < M) {
+        f32x4 w;
+        w.x = st.m;
+        w.y = st.s;
+        w.z = st.t;
+        w.w = __int_as_float(st.idx);
+        o[(int64_t)m * nparts + part] = w;
+      }
+    }
+  }
+}
+
+template <int MT, int NT>
+static hipError_t launch_gemm_mt_nt(const bf16_t* X, const bf16_t* Wp, void* out,
+                                    const float* row_scale, int M, int N, int Kd,
+                                    const GemmPlan& plan, int epi, hipStream_t st) {
+  int ntiles = N / 16;
+  int nblocks = (ntiles + 4 * NT - 1) / (4 * NT);
+  int nchunks = (Kd / 32 + GEMM_KS - 1) / GEMM_KS;
+  int cps = (nchunks + plan.splits - 1) / plan.splits;
+  dim3 grid(nblocks, plan.splits, plan.mblocks), block(256);
+  const u32x4* W4 = (const u32x4*)Wp;
+  if (epi == EPI_PARTIAL) {
+    hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_PARTIAL>), grid, block, 0, st, X, W4, out,
+                       row_scale, M, N, Kd, cps);
+  } else if (epi == EPI_SWIGLU) {
+    if constexpr (NT >= 2) {
+      hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_SWIGLU>), grid, block, 0, st, X, W4, out,
+                         row_scale, M, N, Kd, cps);
+    } else {
+      return hipErrorInvalidValue;
+    }
+  } else {
+    hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_LMHEAD>), grid, block, 0, st, X, W4, out,
+                       row_scale, M, N, Kd, cps);
+  }
+  return hipGetLastError();
+}
+
+template <int MT>
+static hipError_t launch_gemm_mt(const bf16_t* X, const bf16_t* Wp, void* out,
+                                 const float* row_scale, int M, int N, int Kd, const GemmPlan& plan,
+                                 int epi, hipStream_t st) {
+  switch (plan.nt) {
+    case 1: return launch_gemm_mt_nt<MT, 1>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+    case 2: return launch_gemm_mt_nt<MT, 2>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+    case 4:
+      // nine row tiles times four column tiles of accumulators do not fit the register file
+      if constexpr (MT <= 5) return launch_gemm_mt_nt<MT, 4>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+      else return hipErrorInvalidValue;
+  }
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_gemm_bf16(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale,
+                            int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st) {
+  // Host-side shape checks: the kernel assumes whole 16-column tiles and whole
+  // 32-row k-steps, and that the row blocks cover M.
+  if (N % 16 != 0 || Kd % 32 != 0 || M < 1) return hipErrorInvalidValue;
+  if (plan.mblocks * plan.mt * 16 < M) return hipErrorInvalidValue;
+  if (epi != EPI_PARTIAL && plan.splits != 1) return hipErrorInvalidValue;
+  if (epi == EPI_SWIGLU && (N % 32 != 0)) return hipErrorInvalidValue;
+  switch (plan.mt) {
+    case 1: return launch_gemm_mt<1>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+    case 2: return launch_gemm_mt<2>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+    case 3: return launch_gemm_mt<3>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+    case 5: return launch_gemm_mt<5>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+    case 9: return launch_gemm_mt<9>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+int gemm_bf16_lmhead_parts(int N, const GemmPlan& plan) {
+  int ntiles = N / 16;
+  int nblocks = (ntiles + 4 * plan.nt - 1) / (4 * plan.nt);
+  return nblocks * 4;
+}
+
+// ---------------------------------------------------------------------------
+// fp32 GEMM (tiny configuration): block = 64 columns x 4 k-slices, up to 8 rows.
+// ---------------------------------------------------------------------------
+#define F32_MB 8
+
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ X,
+                                                       const float* __restrict__ W,
+                                                       void* __restrict__ out,
+                                                       const float* __restrict__ row_scale, int M,
+                                                       int N, int Kd) {
+  __shared__ float red[4][F32_MB][64];
+  const int c = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int n = blockIdx.x * 64 + c;
+  const int m0 = blockIdx.y * F32_MB;
+  float acc[F32_MB];
+#pragma unroll
+  for (int r = 0; r < F32_MB; ++r) acc[r] = 0.f;
+  if (n < N) {
+    for (int k = slice; k < Kd; k += 4) {
+      float w = W[(int64_t)k * N + n];
+#pragma unroll
+      for (int r = 0; r < F32_MB; ++r) {
+        int m = m0 + r;
+        float x = (m < M) ? X[(int64_t)m * Kd + k] : 0.f;
+        acc[r] = fmaf(x, w, acc[r]);
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < F32_MB; ++r) red[slice][r][c] = acc[r];
+  __syncthreads();
+  // thread (slice, c) finishes rows slice and slice+4 of column c
+#pragma unroll
+  for (int rr = 0; rr < 2; ++rr) {
+    int r = slice + 4 * rr;
+    // rows slice and slice+4 of column c are read and rewritten by this thread only
+    red[0][r][c] = red[0][r][c] + red[1][r][c] + red[2][r][c] + red[3][r][c];
+  }
+  __syncthreads();
+  if constexpr (EPI == EPI_PARTIAL) {
+    float* o = (float*)out;
+#pragma unroll
+    for (int rr = 0; rr < 2; ++rr) {
+      int r = slice + 4 * rr, m = m0 + r;
+      if (m < M && n < N) o[(int64_t)m * N + n] = red[0][r][c];
+    }
+  } else if constexpr (EPI == EPI_SWIGLU) {
+    // 16-column tiles alternate gate / up inside the 64-column block
+    float* o = (float*)out;
+    const int Nh = N / 2;
+    if (c < 32) {  // pair 0 uses tiles (0,1), pair 1 tiles (2,3) of this block
+      const int pair = c >> 4, e = c & 15;
+#pragma unroll
+      for (int rr = 0; rr < 2; ++rr) {
+        int r = slice + 4 * rr, m = m0 + r;
+        int ncol = blockIdx.x * 64 + pair * 32 + e;  // gate column in the packed matrix
+        if (m < M && ncol + 16 < N) {
+          float gt = red[0][r][pair * 32 + e], up = red[0][r][pair * 32 + 16 + e];
+          o[(int64_t)m * Nh + blockIdx.x * 32 + pair * 16 + e] = silu_f(gt) * up;
+        }
+      }
+    }
+  } else {
+    f32x4* o = (f32x4*)out;
+    const int nparts = gridDim.x;
+#pragma unroll
+    for (int rr = 0; rr < 2; ++rr) {
+      int r = slice + 4 * rr, m = m0 + r;
+      float sc = (row_scale != nullptr && m < M) ? row_scale[m] : 1.f;
+      RowStat st = stat_empty();
+      if (n < N) {
+        st.m = red[0][r][c] * sc;
+        st.s = 1.f;
+        st.t = 0.f;
+        st.idx = n;
+      }
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) st = stat_merge(st, stat_shfl_xor(st, off));
+      if (c == 0 && m < M) {
+        f32x4 w;
+        w.x = st.m;
+        w.y = st.s;
+        w.z = st.t;
+        w.w = __int_as_float(st.idx);
+        o[(int64_t)m * nparts + blockIdx.x] = w;
+      }
+    }
+  }
+}
+
+hipError_t launch_gemm_f32(const float* X, const float* W, void* out, const float* row_scale, int M,
+                           int N, int Kd, int epi, hipStream_t st) {
+  if (N % 16 != 0 || M < 1 || Kd < 1) return hipErrorInvalidValue;
+  if (epi == EPI_SWIGLU && N % 32 != 0) return hipErrorInvalidValue;
+  dim3 grid((N + 63) / 64, (M + F32_MB - 1) / F32_MB), block(256);
+  if (epi == EPI_PARTIAL)
+    hipLaunchKernelGGL((gemm_f32_kernel<EPI_PARTIAL>), grid, block, 0, st, X, W, out, row_scale, M, N, Kd);
+  else if (epi == EPI_SWIGLU)
+    hipLaunchKernelGGL((gemm_f32_kernel<EPI_SWIGLU>), grid, block, 0, st, X, W, out, row_scale, M, N, Kd);
+  else
+    hipLaunchKernelGGL((gemm_f32_kernel<EPI_LMHEAD>), grid, block, 0, st, X, W, out, row_scale, M, N, Kd);
+  return hipGetLastError();
+}
+
+int gemm_f32_lmhead_parts(int N) { return (N + 63) / 64; }

@@ -1,0 +1,149 @@
+"""The C-ABI library without a GPU: it loads, exports what include/fly.h
+declares, and every argument check fires before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2511_22972_amd", "libfly.so")
+
+pytestmark = pytest.mark.skipif(not os.path.exists(LIB), reason="libfly.so not built")
+
+
+@pytest.fixture(scope="module")
+def fb():
+    from paper_2511_22972_amd import binding
+    return binding
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "fly.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fly_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(fb):
+    names = declared_functions()
+    assert "fly_verify_block" in names and "fly_lmhead_entropy_argmax" in names and "fly_accept" in names
+    for n in names:
+        assert hasattr(fb.lib, n), n
+    assert sorted(fb.EXPORTS) == names
+
+
+def test_strerror(fb):
+    assert fb.strerror(0) == "ok"
+    seen = {fb.strerror(-i) for i in range(1, 12)}
+    assert len(seen) == 11 and "unknown status" not in seen
+    assert fb.strerror(-99) == "unknown status"
+
+
+def _desc(fb, **kw):
+    base = dict(n_layers=2, d=256, n_q_heads=4, n_kv_heads=2, head_dim=64, ffn=688, vocab=8192,
+                dtype=fb.FLY_F32, rms_eps=1e-5, rope_theta=5e5)
+    base.update(kw)
+    return fb.fly_model_desc(*[base[k] for k, _ in fb.fly_model_desc._fields_])
+
+
+def test_workspace_query_and_shape_errors(fb):
+    out = C.c_size_t(0)
+    d = _desc(fb)
+    assert fb.lib.fly_workspace_bytes(C.byref(d), 1, 4, 128, C.byref(out)) == 0 and out.value > 0
+    small = out.value
+    d16 = _desc(fb, dtype=fb.FLY_BF16, head_dim=128, d=4096, n_q_heads=32, n_kv_heads=8, ffn=14336,
+                vocab=128256, n_layers=32)
+    assert fb.lib.fly_workspace_bytes(C.byref(d16), 1, 8, 2048, C.byref(out)) == 0 and out.value > small
+    assert fb.lib.fly_workspace_bytes(None, 1, 4, 128, C.byref(out)) == -1
+    assert fb.lib.fly_workspace_bytes(C.byref(d), 1, 4, 128, None) == -1
+    assert fb.lib.fly_workspace_bytes(C.byref(d), 0, 4, 128, C.byref(out)) == -2
+    assert fb.lib.fly_workspace_bytes(C.byref(d), 1, 0, 128, C.byref(out)) == -3
+    assert fb.lib.fly_workspace_bytes(C.byref(d), 1, 64, 128, C.byref(out)) == -3
+    assert fb.lib.fly_workspace_bytes(C.byref(_desc(fb, dtype=7)), 1, 4, 128, C.byref(out)) == -6
+    assert fb.lib.fly_workspace_bytes(C.byref(_desc(fb, head_dim=96)), 1, 4, 128, C.byref(out)) == -7
+    assert fb.lib.fly_workspace_bytes(C.byref(_desc(fb, dtype=fb.FLY_BF16, head_dim=64)), 1, 4, 128,
+                                      C.byref(out)) == -7
+    assert fb.lib.fly_workspace_bytes(C.byref(_desc(fb, n_kv_heads=3)), 1, 4, 128, C.byref(out)) == -2
+    assert fb.lib.fly_workspace_bytes(C.byref(_desc(fb, vocab=8200)), 1, 4, 128, C.byref(out)) == -2
+    # more than 384 query rows per KV head cannot be held by one workgroup
+    assert fb.lib.fly_workspace_bytes(C.byref(_desc(fb, dtype=fb.FLY_BF16, head_dim=128, n_q_heads=64,
+                                                    n_kv_heads=1)), 1, 16, 128, C.byref(out)) == -2
+
+
+def test_accept_argument_checks(fb):
+    p = C.c_void_p(4096)   # never dereferenced: every call below fails validation first
+    f = fb.lib.fly_accept
+    assert f(None, p, p, 1, 4, 0.3, 6, p, p, None, None) == -1
+    assert f(p, p, p, 1, 4, 0.3, 6, None, p, None, None) == -1
+    assert f(p, p, p, 0, 4, 0.3, 6, p, p, None, None) == -2
+    assert f(p, p, p, 1, 0, 0.3, 6, p, p, None, None) == -3
+    assert f(p, p, p, 1, 64, 0.3, 6, p, p, None, None) == -3
+    assert f(p, p, p, 1, 4, 0.3, -1, p, p, None, None) == -4
+    assert f(p, p, p, 1, 4, float("nan"), 6, p, p, None, None) == -5
+
+
+def test_lmhead_argument_checks(fb):
+    p, odd = C.c_void_p(4096), C.c_void_p(4100)
+    f = fb.lib.fly_lmhead_entropy_argmax
+    out = C.c_size_t(0)
+    assert fb.lib.fly_lmhead_workspace_bytes(36, 8192, 128256, fb.FLY_BF16, C.byref(out)) == 0
+    need = out.value
+    assert need >= 36 * (128256 // 32) * 16
+    assert f(None, p, None, 36, 8192, 128256, 1, p, p, p, None, p, need, None) == -1
+    assert f(p, p, None, 36, 8192, 128256, 1, p, p, p, None, None, need, None) == -9
+    assert f(p, p, None, 36, 8192, 128256, 1, p, p, p, None, p, need - 1, None) == -9
+    assert f(odd, p, None, 36, 8192, 128256, 1, p, p, p, None, p, need, None) == -8
+    assert f(p, p, None, 36, 8192, 128250, 1, p, p, p, None, p, need, None) == -2
+    assert f(p, p, None, 36, 8200, 128256, 1, p, p, p, None, p, need, None) == -2
+    assert f(p, p, None, 36, 8192, 128256, 5, p, p, p, None, p, need, None) == -6
+    assert f(p, p, None, 0, 8192, 128256, 1, p, p, p, None, p, need, None) == -2
+
+
+def test_verify_block_argument_checks(fb):
+    p = 4096
+    d = _desc(fb)
+    lw = (fb.fly_layer_weights * 2)(*[fb.fly_layer_weights(p, p, p, p, p, p)] * 2)
+    w = fb.fly_weights(p, lw, p, p)
+    karr = (C.c_void_p * 2)(p, p)
+    kv = fb.fly_kv_cache(karr, karr, p, 192, 128)
+    out = fb.fly_verify_out(p, p, p, p, p, p, None, None, None)
+    f = fb.lib.fly_verify_block
+    ws = C.c_size_t(0)
+    fb.lib.fly_workspace_bytes(C.byref(d), 1, 4, 128, C.byref(ws))
+    args = lambda **kw: [kw.get("desc", C.byref(d)), kw.get("w", C.byref(w)), kw.get("kv", C.byref(kv)),
+                         kw.get("tokens", p), None, kw.get("B", 1), kw.get("K", 4),
+                         kw.get("theta", 0.3), kw.get("W", 6), kw.get("out", C.byref(out)),
+                         kw.get("ws", p), kw.get("wsb", ws.value), None]
+    assert f(*args(tokens=None)) == -1
+    assert f(*args(K=70)) == -3
+    assert f(*args(W=-2)) == -4
+    assert f(*args(theta=float("nan"))) == -5
+    assert f(*args(ws=None)) == -9
+    assert f(*args(wsb=ws.value - 1)) == -9
+    assert f(*args(ws=4100)) == -8
+    kv_small = fb.fly_kv_cache(karr, karr, p, 128, 128)          # 128 + 5 rows do not fit
+    assert f(*args(kv=C.byref(kv_small))) == -10
+    kv_odd = fb.fly_kv_cache(karr, karr, p, 200, 128)            # capacity not a multiple of 64
+    assert f(*args(kv=C.byref(kv_odd))) == -2
+    w_null = fb.fly_weights(p, lw, p, None)
+    assert f(*args(w=C.byref(w_null))) == -1
+    lw_bad = (fb.fly_layer_weights * 2)(fb.fly_layer_weights(p, p, p, p, p, p),
+                                        fb.fly_layer_weights(p, 4100, p, p, p, p))
+    assert f(*args(w=C.byref(fb.fly_weights(p, lw_bad, p, p)))) == -8
+    out_null = fb.fly_verify_out(p, None, p, p, p, p, None, None, None)
+    assert f(*args(out=C.byref(out_null))) == -1
+
+
+def test_pack_argument_checks(fb):
+    p = C.c_void_p(4096)
+    out = C.c_size_t(0)
+    assert fb.lib.fly_packed_weight_bytes(8192, 10240, fb.FLY_BF16, C.byref(out)) == 0
+    assert out.value == 8192 * 10240 * 2
+    assert fb.lib.fly_packed_weight_bytes(688, 256, fb.FLY_F32, C.byref(out)) == 0 and out.value == 688 * 256 * 4
+    assert fb.lib.fly_packed_weight_bytes(688, 256, fb.FLY_BF16, C.byref(out)) == -2   # 688 % 32 != 0
+    f = fb.lib.fly_pack_weight
+    assert f(None, 64, 32, 1, p, 32, 0, 1, None) == -1
+    assert f(p, 64, 24, 1, p, 32, 0, 1, None) == -2
+    assert f(p, 64, 32, 1, p, 32, 1, 1, None) == -2      # last tile would fall outside dst
+    assert f(p, 64, 32, 1, p, 64, 2, 2, None) == -2      # tiles 2 and 4 of a 4-tile destination
+    assert f(p, 64, 32, 9, p, 32, 0, 1, None) == -6
