@@ -1,0 +1,184 @@
+"""HIP decoder layers and the whole verification step against the CPU oracle,
+element by element, on seeded synthetic workloads small enough for the oracle
+to finish in seconds but spanning several tiles, ragged tails and ragged
+cache lengths."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import fly_oracle as O
+from tests import helpers
+from tests.gpu_harness import GpuWorkload, ambiguous_rows, compare_verify
+
+pytestmark = pytest.mark.gpu
+
+C1 = synth.CONFIGS["c1_tiny"]
+# bf16 shapes: small multiples of the kernels' tiles, with ragged row counts
+B16_SMALL = synth.CONFIGS["c2_8b"].replace(
+    name="bf16_small", n_layers=2, d=256, n_q_heads=4, n_kv_heads=2, ffn=512, vocab=2048,
+    batch=2, K=4, kv_len=150, weight_std=0.05)
+B16_WIDE = synth.CONFIGS["c2_8b"].replace(
+    name="bf16_wide", n_layers=2, d=512, n_q_heads=16, n_kv_heads=2, ffn=1056, vocab=4112,
+    batch=3, K=8, kv_len=300, weight_std=0.04, temperatures=(0.3, 1.0, 3.0), logit_gain=3.0)
+
+
+def oracle_model_from_gpu(cfg):
+    """Oracle-side fp64 copies of the same seeded tensors (generated on the GPU
+    by the shared generator, which is bit-identical to the CPU one)."""
+    return helpers.oracle_model(cfg, device="cuda")
+
+
+def ragged_prefix(model, kv_lens):
+    """Per-sequence prefixes of different lengths for the oracle."""
+    out = []
+    for k, v in model["kv_prefix"]:
+        out.append(([k[b, :L] for b, L in enumerate(kv_lens)], [v[b, :L] for b, L in enumerate(kv_lens)]))
+    return out
+
+
+def run_layers_case(cfg, kv_lens, x_std=1.0):
+    """fly_decoder_layers on a random residual stream vs the oracle's layers."""
+    wl = GpuWorkload(cfg, kv_lens=kv_lens)
+    fb = wl.fb
+    M = cfg.M
+    x0 = synth.hash_normal(cfg.seed, 300, (M, cfg.d), x_std, torch.float32, "cuda")
+    x = x0.clone()
+    fb.fly_decoder_layers(wl.model, wl.kv, x, 0, cfg.n_layers, cfg.batch, cfg.K, wl.ws)
+    torch.cuda.synchronize()
+    got = x.cpu().double().numpy().reshape(cfg.batch, cfg.K + 1, cfg.d)
+
+    model = oracle_model_from_gpu(cfg)
+    prefix = ragged_prefix(model, kv_lens)
+    num = O.Numerics(cfg.dtype)
+    ref = np.zeros_like(got)
+    new_kv = []
+    for b in range(cfg.batch):
+        xb = x0.cpu().double().view(cfg.batch, cfg.K + 1, cfg.d)[b]
+        per_layer = []
+        for li, w in enumerate(model["layers"]):
+            xb, k_new, v_new = O.decoder_layer(xb, w, prefix[li][0][b], prefix[li][1][b], cfg.n_q_heads,
+                                               cfg.n_kv_heads, cfg.head_dim, cfg.rope_theta, cfg.rms_eps, num)
+            per_layer.append((k_new, v_new))
+        ref[b] = xb.numpy()
+        new_kv.append(per_layer)
+    return wl, got, ref, new_kv
+
+
+def check_appended_kv(wl, cfg, kv_lens, new_kv, tol):
+    """Rows kv_len..kv_len+K of every layer's cache hold the oracle's new k, v."""
+    for li in range(cfg.n_layers):
+        kc = wl.kv.k[li].float().cpu().double()          # [B,Hkv,cap,hd]
+        vc = wl.kv.v[li].float().cpu().double()          # [B,Hkv,hd,cap]
+        for b, L in enumerate(kv_lens):
+            k_new, v_new = new_kv[b][li]                 # [R,Hkv,hd]
+            got_k = kc[b, :, L:L + cfg.K + 1, :].permute(1, 0, 2)
+            got_v = vc[b, :, :, L:L + cfg.K + 1].permute(2, 0, 1)
+            assert (got_k - k_new).abs().max().item() <= tol, ("k", li, b)
+            assert (got_v - v_new).abs().max().item() <= tol, ("v", li, b)
+
+
+def test_layers_f32_tiny():
+    cfg = C1.replace(batch=2, K=4)
+    kv_lens = [128, 77]
+    wl, got, ref, new_kv = run_layers_case(cfg, kv_lens)
+    assert np.abs(got - ref).max() < 1e-4
+    check_appended_kv(wl, cfg, kv_lens, new_kv, 1e-5)
+
+
+@pytest.mark.parametrize("cfg,kv_lens", [(B16_SMALL, [150, 64]), (B16_WIDE, [300, 1, 129])])
+def test_layers_bf16(cfg, kv_lens):
+    wl, got, ref, new_kv = run_layers_case(cfg, kv_lens)
+    # residual stream is fp32 on the device; both sides round the same tensors to bf16
+    scale = np.abs(ref).max()
+    assert np.abs(got - ref).max() < 2e-2 * max(1.0, scale / 4)
+    # appended keys/values are bf16 values: equal up to one bf16 ulp at rounding boundaries
+    check_appended_kv(wl, cfg, kv_lens, new_kv, 2e-2)
+
+
+def test_layers_bf16_single_row_tile_edges():
+    """M = 17 rows (one full 16-row tile plus one) and 136 rows (nine tiles)."""
+    for batch, K in ((1, 16), (8, 16)):
+        cfg = B16_SMALL.replace(batch=batch, K=K, n_layers=1, kv_len=70)
+        wl, got, ref, _ = run_layers_case(cfg, [70] * batch)
+        assert np.abs(got - ref).max() < 2e-2
+
+
+def verify_case(cfg, theta=None, W=None):
+    model = oracle_model_from_gpu(cfg)
+    tokens = helpers.draft_chain(cfg, model)
+    ora = helpers.oracle_verify(cfg, model, tokens, theta=theta, W=W)
+    wl = GpuWorkload(cfg)
+    gpu = wl.verify(tokens, helpers.row_scale(cfg), theta=theta, W=W)
+    return wl, tokens, gpu, ora
+
+
+def test_verify_c1_tiny_fp32():
+    """The tiny fp32 configuration end to end, free-running."""
+    cfg = C1
+    wl, tokens, gpu, ora = verify_case(cfg)
+    err = compare_verify(gpu, ora, cfg.theta, 1e-4, O.accept_block)
+    # with W = 6 and K = 4 no window fits: the rule is exact-match decoding here
+    std = np.array([O.s_standard(O.match_indicator(tokens[b, 1:], ora["argmax"][b])) for b in range(cfg.batch)])
+    assert np.array_equal(ora["s"], std)
+    assert np.array_equal(gpu["kv_len_out"], cfg.kv_len + gpu["accept_len"] + 1)
+    assert err["n_clean_sequences"] >= 1
+
+
+@pytest.mark.parametrize("W", [0, 1, 2])
+def test_verify_c1_with_fitting_windows(W):
+    """Same model with a logit gain so both gate branches occur, windows that fit K = 4,
+    and a batch of sequences."""
+    cfg = C1.replace(batch=6, logit_gain=12.0, window=W)
+    wl, tokens, gpu, ora = verify_case(cfg)
+    compare_verify(gpu, ora, cfg.theta, 1e-4, O.accept_block)
+    assert ora["h"][:, :-1].min() < cfg.theta < ora["h"][:, :-1].max()
+    # the rule applied to the device's own statistics reproduces the device's decision
+    own = O.accept_block(tokens[:, 1:], gpu["argmax"], gpu["h_norm"], cfg.theta, W)
+    for k in ("accept_len", "next_token", "n_loose"):
+        assert np.array_equal(gpu[k], own[k])
+
+
+@pytest.mark.parametrize("cfg", [B16_SMALL, B16_WIDE])
+def test_verify_bf16_small(cfg):
+    cfg = cfg.replace(window=2)
+    wl, tokens, gpu, ora = verify_case(cfg)
+    compare_verify(gpu, ora, cfg.theta, 2e-2, O.accept_block)
+    own = O.accept_block(tokens[:, 1:], gpu["argmax"], gpu["h_norm"], cfg.theta, cfg.window)
+    for k in ("accept_len", "next_token", "n_loose"):
+        assert np.array_equal(gpu[k], own[k])
+    assert np.array_equal(gpu["kv_len_out"], cfg.kv_len + gpu["accept_len"] + 1)
+
+
+def test_verify_limits_on_device():
+    """theta > 1 gives exact-match decoding; theta = 0 with W = 0 accepts everything."""
+    cfg = B16_SMALL.replace(batch=4, K=8)
+    model = oracle_model_from_gpu(cfg)
+    tokens = helpers.draft_chain(cfg, model)
+    wl = GpuWorkload(cfg)
+    rs = helpers.row_scale(cfg)
+    strict = wl.verify(tokens, rs, theta=2.0, W=6)
+    std = np.array([O.s_standard(O.match_indicator(tokens[b, 1:], strict["argmax"][b])) for b in range(cfg.batch)])
+    assert np.array_equal(strict["accept_len"] + 1, std)
+    # re-running on the same cache rewrites the same rows: results are reproducible bit for bit
+    again = wl.verify(tokens, rs, theta=2.0, W=6)
+    for k in strict:
+        assert np.array_equal(strict[k], again[k]), k
+    loose = wl.verify(tokens, rs, theta=0.0, W=0)
+    assert np.all(loose["accept_len"] == cfg.K)
+    assert np.array_equal(loose["next_token"], loose["argmax"][:, -1])
+
+
+def test_causality_on_device():
+    """Changing drafts from position 3 on leaves the statistics of rows 0..2 untouched."""
+    cfg = B16_SMALL
+    wl = GpuWorkload(cfg)
+    rng = np.random.default_rng(0)
+    tokens = rng.integers(0, cfg.vocab, size=(cfg.batch, cfg.K + 1)).astype(np.int32)
+    a = wl.verify(tokens, None)
+    t2 = tokens.copy()
+    t2[:, 3:] = (t2[:, 3:] + 1) % cfg.vocab
+    b = wl.verify(t2, None)
+    for k in ("argmax", "h_norm", "p_top1", "lse"):
+        assert np.array_equal(a[k][:, :3], b[k][:, :3]), k
+    assert not np.array_equal(a["lse"][:, 3:], b["lse"][:, 3:])
