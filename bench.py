@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the FLy verification step on one MI355X.
+
+One "step" is one whole verification pass (embedding, all decoder layers with
+KV append and attention, final norm, LM head with fused row statistics,
+acceptance rule) over one block of B x (K+1) synthetic tokens.  Inputs are
+resident in HBM before the timed region.  Prints one JSON line.
+
+    python bench.py [--workload c3_70b] [--steps 20] [--warmup 5] [--gpus 1]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+import synth
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_gpu_workload(cfg):
+    from paper_2511_22972_amd import binding as fb
+    t0 = time.time()
+    desc = fb.make_desc(cfg)
+    model = fb.PackedModel(desc, lambda name, layer: synth.make_weight(cfg, name, layer, "cuda"))
+    log(f"[bench] weights generated and packed in {time.time() - t0:.1f}s")
+    cap = (cfg.kv_len + cfg.K + 1 + 63) // 64 * 64
+    kv = fb.KVCache(desc, cfg.batch, cap)
+    for l in range(cfg.n_layers):
+        k, v = synth.make_kv_prefix(cfg, l, "cuda")
+        kv.load_prefix(l, k, v)
+    kv.set_lengths([cfg.kv_len] * cfg.batch)
+    ws = fb.alloc_workspace(fb.fly_workspace_bytes(desc, cfg.batch, cfg.K, cfg.kv_len))
+    torch.cuda.synchronize()
+    log(f"[bench] KV cache ready, total setup {time.time() - t0:.1f}s, "
+        f"HBM in use {torch.cuda.memory_allocated() / 2**30:.1f} GiB")
+    return fb, desc, model, kv, ws
+
+
+def device_draft_chain(fb, cfg, model, kv, ws, row_scale):
+    """Draft tokens for the timed block: draft i equals the target's argmax at
+    position i with probability p_match, else a uniform token.  The chain is
+    built with K+1 untimed passes of the verification step itself (row i's
+    argmax does not depend on later tokens)."""
+    first = synth.make_first_tokens(cfg, "cuda")
+    u, alt, _ = synth.make_draft_draws(cfg, "cuda")
+    tokens = torch.zeros(cfg.batch, cfg.K + 1, dtype=torch.int32, device="cuda")
+    tokens[:, 0] = first
+    out = fb.VerifyOutputs(cfg.batch, cfg.K)
+    for i in range(1, cfg.K + 1):
+        fb.fly_verify_block(model, kv, tokens, row_scale, cfg.theta, cfg.window, out, ws)
+        y = out.argmax[:, i - 1]
+        tokens[:, i] = torch.where(u[:, i - 1] < cfg.p_match, y, alt[:, i - 1])
+    torch.cuda.synchronize()
+    return tokens
+
+
+def algorithmic_bytes(cfg):
+    """Bytes one verification step must move: every weight once, the visible
+    cache once, plus the (small) activations."""
+    es = 2 if cfg.dtype == "bf16" else 4
+    per_layer = sum(a * b for a, b in synth.layer_weight_shapes(cfg).values()) * es
+    lm = cfg.d * cfg.vocab * es
+    kvb = 2 * cfg.batch * (cfg.kv_len + cfg.K + 1) * cfg.kv_dim * es * cfg.n_layers
+    return {"layer_weights": per_layer * cfg.n_layers, "lm_head": lm, "kv": kvb,
+            "total": per_layer * cfg.n_layers + lm + kvb}
+
+
+def time_region(fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    start = torch.cuda.Event(enable_timing=True)
+    end = torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(steps):
+        fn()
+    end.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(end) / steps  # ms per call
+
+
+def cpu_baseline(cfg, tokens_np, layers_sampled=1):
+    """The oracle timed on this host on a bounded sample: `layers_sampled`
+    decoder layers plus the LM head, row statistics and acceptance rule for the
+    whole block; the full step is extrapolated as n_layers x layer + head."""
+    from oracle import fly_oracle as O
+    from tests import helpers
+    B, R = tokens_np.shape
+    num = O.Numerics(cfg.dtype)
+    f64 = lambda t: t.to("cpu", torch.float64)
+    x0 = f64(synth.make_hidden(cfg, B * R, "cuda")).view(B, R, cfg.d)
+    t_layer = 0.0
+    for l in range(layers_sampled):
+        w = helpers.oracle_layer_weights(cfg, l, "cuda")
+        kp, vp = (f64(t) for t in synth.make_kv_prefix(cfg, l, "cuda"))
+        t0 = time.perf_counter()
+        for b in range(B):
+            O.decoder_layer(x0[b], w, kp[b], vp[b], cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                            cfg.rope_theta, cfg.rms_eps, num)
+        t_layer += time.perf_counter() - t0
+        del w, kp, vp
+    t_layer /= layers_sampled
+    w_lm = f64(synth.make_weight(cfg, "w_lm", -1, "cuda"))
+    g = f64(synth.make_weight(cfg, "g_final", -1, "cuda"))
+    rs = (1.0 / synth.make_row_temperature(cfg)).reshape(-1)
+    t0 = time.perf_counter()
+    xn = num.act(O.rmsnorm(x0.reshape(B * R, cfg.d), g, cfg.rms_eps))
+    stats = O.decision_statistics(O.lm_head_logits(xn, w_lm, rs))
+    acc = O.accept_block(tokens_np[:, 1:], stats["argmax"].reshape(B, R), stats["h"].reshape(B, R),
+                         cfg.theta, cfg.window)
+    t_head = time.perf_counter() - t0
+    total = cfg.n_layers * t_layer + t_head
+    return {"t_layer_s": t_layer, "t_head_s": t_head, "t_step_s": total,
+            "sample": f"{layers_sampled} of {cfg.n_layers} decoder layers + LM head + row statistics + "
+                      f"acceptance for all {B * R} rows; step = n_layers x layer + head"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c3_70b", choices=sorted(synth.CONFIGS))
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)",
+              file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.workload]
+    if args.layers:
+        cfg = cfg.replace(n_layers=args.layers)
+
+    fb, desc, model, kv, ws = build_gpu_workload(cfg)
+    row_scale = (1.0 / synth.make_row_temperature(cfg, "cuda")).reshape(-1).contiguous()
+    tokens = device_draft_chain(fb, cfg, model, kv, ws, row_scale)
+    out = fb.VerifyOutputs(cfg.batch, cfg.K)
+
+    def step():
+        fb.fly_verify_block(model, kv, tokens, row_scale, cfg.theta, cfg.window, out, ws)
+
+    ms = time_region(step, args.steps, args.warmup)
+    accept_len = out.accept_len.cpu().numpy()
+    s_total = int((accept_len + 1).sum())          # the paper's count: kept drafts + 1
+    tokens_per_s = s_total / (ms * 1e-3)
+    ab = algorithmic_bytes(cfg)
+
+    # Dominant kernel: the gate/up GEMM with fused SwiGLU (about 55% of a layer's
+    # bytes), timed alone with events on the launch stream, cycling through the
+    # layers so no launch finds its weights in cache.
+    es = 2 if cfg.dtype == "bf16" else 4
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    xn = synth.make_hidden(cfg, cfg.M, "cuda")
+    a_buf = torch.empty(cfg.M, cfg.ffn, dtype=tdt, device="cuda")
+    gu_ptrs = [model.layers_c[l].w_gateup for l in range(cfg.n_layers)]
+    counter = [0]
+    import ctypes as C
+
+    def gateup():
+        l = counter[0] % cfg.n_layers
+        counter[0] += 1
+        rc = fb.lib.fly_gateup_swiglu(xn.data_ptr(), gu_ptrs[l], a_buf.data_ptr(), cfg.M, cfg.d,
+                                      cfg.ffn, desc.dtype, torch.cuda.current_stream().cuda_stream)
+        assert rc == 0, rc
+
+    gu_ms = time_region(gateup, max(args.steps, 20) * 4, 8)
+    gu_bytes = cfg.d * 2 * cfg.ffn * es + cfg.M * cfg.d * es + cfg.M * cfg.ffn * es
+    gu_gbs = gu_bytes / (gu_ms * 1e-3) / 1e9
+
+    res = {
+        "metric": "verified tokens/s (FLy verify step)", "value": tokens_per_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "verify_step_us": ms * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "n_layers": cfg.n_layers, "d": cfg.d, "heads": f"{cfg.n_q_heads}q/{cfg.n_kv_heads}kv",
+                   "ffn": cfg.ffn, "vocab": cfg.vocab, "batch": cfg.batch, "K": cfg.K,
+                   "kv_len": cfg.kv_len, "theta": cfg.theta, "W": cfg.window, "rows": cfg.M,
+                   "accepted_tokens_per_step": s_total},
+        "step_hbm": {"algorithmic_bytes": ab["total"], "achieved_GBps": ab["total"] / (ms * 1e-3) / 1e9,
+                     "frac_of_peak": ab["total"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "roofline": {"kernel": "gemm_bf16_kernel (gate/up projection + SwiGLU)" if cfg.dtype == "bf16"
+                     else "gemm_f32_kernel (gate/up projection + SwiGLU)",
+                     "bound": "hbm", "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": gu_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": gu_bytes, "avg_launch_us": gu_ms * 1e3},
+    }
+    if not args.no_cpu_baseline:
+        torch.cuda.synchronize()
+        cb = cpu_baseline(cfg, tokens.cpu().numpy())
+        res["cpu_baseline"] = {"value": s_total / cb["t_step_s"], "unit": "tokens/s",
+                               "cores": torch.get_num_threads(), "kind": "oracle", "sample": cb["sample"],
+                               "oracle_step_s_extrapolated": cb["t_step_s"],
+                               "oracle_layer_s": cb["t_layer_s"], "oracle_head_s": cb["t_head_s"]}
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

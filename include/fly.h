@@ -209,6 +209,17 @@ fly_status fly_accept(const int32_t* draft, const int32_t* tgt_argmax, const flo
                       int32_t* next_token, int32_t* n_loose, fly_stream stream);
 
 /*
+ * Gate/up projection with the SwiGLU product fused into the GEMM epilogue
+ * (the widest GEMM of a layer; exposed for per-kernel timing and checks):
+ *   a[m, f] = silu(xn[m] . Wg[:, f]) * (xn[m] . Wu[:, f])
+ *   xn        [device] [M, d] model dtype
+ *   w_gateup  [device] packed [d, 2F], 16-column tiles alternating gate / up
+ *   a         [device] [M, F] model dtype
+ */
+fly_status fly_gateup_swiglu(const void* xn, const void* w_gateup, void* a, int32_t M, int32_t d,
+                             int32_t F, int32_t dtype, fly_stream stream);
+
+/*
  * (K+1)-query causal grouped-query attention against the cache of one layer
  * (exposed for the long-cache workload and for per-kernel timing).
  *   q  [device] [M, Hq*hd] model dtype, already rotated

@@ -274,6 +274,9 @@ def silu(x: torch.Tensor) -> torch.Tensor:
     return x / (1.0 + torch.exp(-x))
 
 
+LOG2E = 1.4426950408889634  # log2(e)
+
+
 def attention_one_sequence(q: torch.Tensor, k_all: torch.Tensor, v_all: torch.Tensor,
                            prefix_len: int, num: Numerics) -> torch.Tensor:
     """Causal grouped-query attention for the K+1 new rows of one sequence.
@@ -293,10 +296,14 @@ def attention_one_sequence(q: torch.Tensor, k_all: torch.Tensor, v_all: torch.Te
         scores = (q[:, a, :] @ kh.T) / math.sqrt(hd)  # [R, T]
         for i in range(R):
             visible = key_pos <= prefix_len + i
-            s = scores[i][visible]
-            e = torch.exp(s - s.max())
-            # The device multiplies bf16 probabilities into V and normalises
-            # by the unrounded sum afterwards.
+            s2 = scores[i][visible] * LOG2E              # exponent in base 2
+            # softmax(s) = 2^(s2 - n) / sum 2^(s2 - n) for ANY n.  The device
+            # multiplies bf16 probabilities into V, so the unnormalised terms are
+            # rounded to bf16; they are taken relative to the integer n = ceil(max s2)
+            # (a power-of-two scaling, under which bf16 rounding is exact), and
+            # the normalising sum uses the unrounded terms.
+            n = torch.ceil(s2.max())
+            e = torch.exp2(s2 - n)
             out[i, a, :] = (num.act(e) @ vh[visible]) / e.sum()
     return out
 

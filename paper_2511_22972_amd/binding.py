@@ -22,7 +22,7 @@ FLY_F32, FLY_BF16 = 0, 1
 EXPORTS = [
     "fly_strerror", "fly_set_tuning", "fly_packed_weight_bytes", "fly_pack_weight",
     "fly_workspace_bytes", "fly_lmhead_workspace_bytes", "fly_verify_block", "fly_decoder_layers",
-    "fly_lmhead_entropy_argmax", "fly_accept", "fly_attention",
+    "fly_lmhead_entropy_argmax", "fly_accept", "fly_attention", "fly_gateup_swiglu",
 ]
 
 
@@ -91,6 +91,8 @@ def _load() -> C.CDLL:
     lib.fly_attention.argtypes = [C.POINTER(fly_model_desc), C.POINTER(fly_kv_cache), C.c_int32,
                                   C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t,
                                   C.c_void_p]
+    lib.fly_gateup_swiglu.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                      C.c_int32, C.c_int32, C.c_void_p]
     for name in EXPORTS:
         if name != "fly_strerror":
             getattr(lib, name).restype = C.c_int
@@ -323,6 +325,13 @@ def fly_attention(desc: fly_model_desc, kv: KVCache, layer: int, q: torch.Tensor
     _check(lib.fly_attention(C.byref(desc), C.byref(kvs), layer, _ptr(q), _ptr(o), B, K,
                              _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
            "fly_attention")
+
+
+def fly_gateup_swiglu(xn: torch.Tensor, w_gateup_packed: torch.Tensor, a: torch.Tensor) -> None:
+    M, d = xn.shape
+    F = a.shape[1]
+    _check(lib.fly_gateup_swiglu(_ptr(xn), _ptr(w_gateup_packed), _ptr(a), M, d, F,
+                                 dtype_code(xn.dtype), _stream()), "fly_gateup_swiglu")
 
 
 def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:

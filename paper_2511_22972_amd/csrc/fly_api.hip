@@ -108,7 +108,7 @@ fly_status check_desc(const fly_model_desc* desc) {
 }
 
 fly_status check_block(int B, int K) {
-  if (B < 1 || B > 4096) return FLY_ERR_BAD_SHAPE;
+  if (B < 1 || B > (1 << 20)) return FLY_ERR_BAD_SHAPE;
   if (K < 1 || K > 63) return FLY_ERR_K_RANGE;
   return FLY_OK;
 }
@@ -439,6 +439,17 @@ fly_status fly_attention(const fly_model_desc* desc, const fly_kv_cache* kv, int
                                  (const float*)kv->v_layers[layer], kv->kv_len, (float*)o, B, K,
                                  desc->n_q_heads, desc->n_kv_heads, desc->head_dim, kv->capacity, st));
   return FLY_OK;
+}
+
+fly_status fly_gateup_swiglu(const void* xn, const void* w_gateup, void* a, int32_t M, int32_t d,
+                             int32_t F, int32_t dtype, fly_stream stream) {
+  if (!xn || !w_gateup || !a) return FLY_ERR_NULL_POINTER;
+  if (dtype != FLY_F32 && dtype != FLY_BF16) return FLY_ERR_DTYPE;
+  if (M < 1 || d < 16 || F < 16 || F % 16 != 0) return FLY_ERR_BAD_SHAPE;
+  if (dtype == FLY_BF16 && d % 32 != 0) return FLY_ERR_BAD_SHAPE;
+  if (!aligned16(xn) || !aligned16(w_gateup) || !aligned16(a)) return FLY_ERR_ALIGNMENT;
+  GemmPlan plan = dtype == FLY_BF16 ? plan_gemm(M, 2 * F, d, false, true) : GemmPlan{1, 1, 1, 1};
+  return run_gemm(dtype, xn, w_gateup, a, nullptr, M, 2 * F, d, plan, EPI_SWIGLU, (hipStream_t)stream);
 }
 
 fly_status fly_verify_block(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,

@@ -193,7 +193,12 @@ __global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
                                                              sacc[kt], 0, 0, 0);
         }
       }
-      // mask, scale, running max
+      // Mask and move to the base-2 exponent domain: s' = (q.k) * scale * log2(e).
+      // Probabilities are formed relative to an INTEGER exponent n >= max s'
+      // (n = ceil of the running maximum): when the maximum grows, earlier
+      // terms are rescaled by an exact power of two, which commutes with the
+      // bf16 rounding of P.  The result is therefore the same as rounding
+      // 2^(s' - n_final) once, independent of how the cache is chunked or split.
       float mx = -INFINITY;
 #pragma unroll
       for (int kt = 0; kt < 4; ++kt)
@@ -206,17 +211,17 @@ __global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
         }
       mx = fmaxf(mx, __shfl_xor(mx, 16, FLY_WAVE));
       mx = fmaxf(mx, __shfl_xor(mx, 32, FLY_WAVE));
-      float mnew = fmaxf(mrun[t], mx);
-      // rows with nothing visible yet keep m = -inf; avoid inf - inf
+      float mnew = fmaxf(mrun[t], ceilf(mx));
+      // rows with nothing visible yet keep n = -inf; avoid inf - inf
       float msafe = (mnew == -INFINITY) ? 0.f : mnew;
-      float corr = __expf(mrun[t] - msafe);  // mrun = -inf -> 0
+      float corr = exp2f(mrun[t] - msafe);  // exact power of two (0 when mrun = -inf)
       mrun[t] = mnew;
       float lsum = 0.f;
       uint32_t pb[4][2];  // bf16 pairs: P[key 16*kt + 4g + {0,1}], {2,3}
 #pragma unroll
       for (int kt = 0; kt < 4; ++kt) {
-        float p0 = __expf(sacc[kt][0] - msafe), p1 = __expf(sacc[kt][1] - msafe);
-        float p2 = __expf(sacc[kt][2] - msafe), p3 = __expf(sacc[kt][3] - msafe);
+        float p0 = exp2f(sacc[kt][0] - msafe), p1 = exp2f(sacc[kt][1] - msafe);
+        float p2 = exp2f(sacc[kt][2] - msafe), p3 = exp2f(sacc[kt][3] - msafe);
         lsum += (p0 + p1) + (p2 + p3);
         pb[kt][0] = pack_bf2(p0, p1);
         pb[kt][1] = pack_bf2(p2, p3);
@@ -277,7 +282,7 @@ __global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
   }
 }
 
-// Merge the splits: o = sum_s O_s e^(m_s - m) / sum_s l_s e^(m_s - m).
+// Merge the splits: o = sum_s O_s 2^(n_s - n) / sum_s l_s 2^(n_s - n), n = max_s n_s.
 // grid (R, B*Hkv), block 128 (one thread per head-dim element).
 __global__ __launch_bounds__(ATT_HD) void attention_combine_kernel(const float* __restrict__ ws,
                                                                    bf16_t* __restrict__ o, int K,
@@ -295,7 +300,7 @@ __global__ __launch_bounds__(ATT_HD) void attention_combine_kernel(const float* 
     float ms = sb[(int64_t)R * ATT_HD + r];
     float ls = sb[(int64_t)R * ATT_HD + R + r];
     if (ls > 0.f) {
-      float w = __expf(ms - mx);
+      float w = exp2f(ms - mx);  // integer exponents: an exact power of two
       num += sb[(int64_t)r * ATT_HD + e] * w;
       den += ls * w;
     }
@@ -317,7 +322,7 @@ hipError_t launch_attention_bf16(const bf16_t* q, const bf16_t* kcache, const bf
   int nw = p.nwaves <= 4 ? 4 : 8;
   dim3 grid(p.nsplit, B * Hkv), block(nw * 64);
   size_t smem = 2 * ATT_STAGE_BYTES;
-  float scale = 1.0f / sqrtf((float)hd);
+  float scale = (float)(1.4426950408889634 / sqrt((double)hd));  // log2(e) / sqrt(hd)
 #define FLY_ATT_LAUNCH(QTW_, NW_)                                                                   \
   hipLaunchKernelGGL((attention_bf16_kernel<QTW_, NW_>), grid, block, smem, st, q, kcache, vcache,   \
                      kv_len, ws, K, Hq, Hkv, capacity, p.chunk_keys, scale)

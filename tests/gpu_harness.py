@@ -71,6 +71,7 @@ def compare_verify(gpu: Dict[str, np.ndarray], ora: Dict[str, np.ndarray], theta
         "h": float(np.abs(gpu["h_norm"] - ora["h"]).max()),
         "p_top1": float(np.abs(gpu["p_top1"] - ora["p_top1"]).max()),
     }
+    print("parity errors", err, "tol", float_tol)
     for k, v in err.items():
         assert v <= float_tol, (k, v, float_tol)
     same = gpu["argmax"] == ora["argmax"]

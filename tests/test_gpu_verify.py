@@ -20,7 +20,7 @@ B16_SMALL = synth.CONFIGS["c2_8b"].replace(
     batch=2, K=4, kv_len=150, weight_std=0.05)
 B16_WIDE = synth.CONFIGS["c2_8b"].replace(
     name="bf16_wide", n_layers=2, d=512, n_q_heads=16, n_kv_heads=2, ffn=1056, vocab=4112,
-    batch=3, K=8, kv_len=300, weight_std=0.04, temperatures=(0.3, 1.0, 3.0), logit_gain=3.0)
+    batch=3, K=8, kv_len=300, weight_std=0.04, temperatures=(0.3, 1.0, 3.0))
 
 
 def oracle_model_from_gpu(cfg):
@@ -90,8 +90,8 @@ def test_layers_f32_tiny():
 def test_layers_bf16(cfg, kv_lens):
     wl, got, ref, new_kv = run_layers_case(cfg, kv_lens)
     # residual stream is fp32 on the device; both sides round the same tensors to bf16
-    scale = np.abs(ref).max()
-    assert np.abs(got - ref).max() < 2e-2 * max(1.0, scale / 4)
+    print("layer max abs err", np.abs(got - ref).max(), "max |ref|", np.abs(ref).max())
+    assert np.abs(got - ref).max() < 2e-2
     # appended keys/values are bf16 values: equal up to one bf16 ulp at rounding boundaries
     check_appended_kv(wl, cfg, kv_lens, new_kv, 2e-2)
 
@@ -101,6 +101,7 @@ def test_layers_bf16_single_row_tile_edges():
     for batch, K in ((1, 16), (8, 16)):
         cfg = B16_SMALL.replace(batch=batch, K=K, n_layers=1, kv_len=70)
         wl, got, ref, _ = run_layers_case(cfg, [70] * batch)
+        print("layer max abs err", np.abs(got - ref).max(), "max |ref|", np.abs(ref).max())
         assert np.abs(got - ref).max() < 2e-2
 
 
@@ -182,3 +183,53 @@ def test_causality_on_device():
     for k in ("argmax", "h_norm", "p_top1", "lse"):
         assert np.array_equal(a[k][:, :3], b[k][:, :3]), k
     assert not np.array_equal(a["lse"][:, 3:], b["lse"][:, 3:])
+
+
+def test_attention_stage_bf16():
+    """fly_attention alone on seeded q and cache: one rounding (the bf16 output)
+    separates the two sides, so elements agree to one bf16 ulp and almost all
+    are identical.  Covers ragged lengths, a cache that ends mid-tile, and 72
+    query rows per KV head over several cache splits."""
+    from paper_2511_22972_amd import binding as fb
+    cfg = synth.CONFIGS["c3_70b"].replace(n_layers=1, n_q_heads=16, n_kv_heads=2, batch=3, K=8,
+                                          kv_len=1000)
+    kv_lens = [1000, 517, 3]
+    R = cfg.K + 1
+    desc = fb.make_desc(cfg)
+    kv = fb.KVCache(desc, cfg.batch, 1024)
+    k, v = synth.make_kv_prefix(cfg.replace(kv_len=1024), 0, "cuda")    # rows beyond kv_len stand for the new rows
+    kv.load_prefix(0, k, v)
+    kv.set_lengths(kv_lens)
+    q = synth.hash_normal(cfg.seed, 310, (cfg.M, cfg.q_dim), 2.0, torch.bfloat16, "cuda")
+    o = torch.zeros_like(q)
+    ws = fb.alloc_workspace(fb.fly_workspace_bytes(desc, cfg.batch, cfg.K, max(kv_lens)))
+    fb.fly_attention(desc, kv, 0, q, o, cfg.batch, cfg.K, ws)
+    torch.cuda.synchronize()
+    got = o.float().cpu().double().view(cfg.batch, R, cfg.n_q_heads, cfg.head_dim)
+    num = O.Numerics("bf16")
+    for b, L in enumerate(kv_lens):
+        qb = q.float().cpu().double().view(cfg.batch, R, cfg.n_q_heads, cfg.head_dim)[b]
+        ref = num.act(O.attention_one_sequence(qb, k[b, :L + R].cpu().double(), v[b, :L + R].cpu().double(), L, num))
+        diff = (got[b] - ref).abs()
+        assert torch.all(diff <= ref.abs() * 2.0 ** -7 + 1e-6), (b, diff.max())
+        assert (diff == 0).double().mean().item() > 0.97, (b, (diff == 0).double().mean().item())
+
+
+def test_gateup_swiglu_stage_bf16():
+    """The fused gate/up GEMM + SwiGLU alone (ragged M, F not a multiple of the block)."""
+    from paper_2511_22972_amd import binding as fb
+    for M, d, F in ((36, 512, 1056), (9, 256, 512), (100, 128, 16 * 37)):
+        x = synth.hash_normal(5, 320, (M, d), 1.0, torch.bfloat16, "cuda")
+        wg = synth.hash_normal(5, 321, (d, F), 0.05, torch.bfloat16, "cuda")
+        wu = synth.hash_normal(5, 322, (d, F), 0.05, torch.bfloat16, "cuda")
+        wp = torch.empty(d * 2 * F, dtype=torch.bfloat16, device="cuda")
+        fb.fly_pack_weight(wg, wp, 2 * F, 0, 2)
+        fb.fly_pack_weight(wu, wp, 2 * F, 1, 2)
+        a = torch.zeros(M, F, dtype=torch.bfloat16, device="cuda")
+        fb.fly_gateup_swiglu(x, wp, a)
+        torch.cuda.synchronize()
+        xd = x.float().cpu().double()
+        ref = O.round_to_bf16(O.silu(xd @ wg.float().cpu().double()) * (xd @ wu.float().cpu().double()))
+        diff = (a.float().cpu().double() - ref).abs()
+        assert torch.all(diff <= ref.abs() * 2.0 ** -7 + 1e-7), (M, d, F, diff.max())
+        assert (diff == 0).double().mean().item() > 0.99
