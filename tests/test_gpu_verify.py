@@ -211,7 +211,11 @@ def test_attention_stage_bf16():
         qb = q.float().cpu().double().view(cfg.batch, R, cfg.n_q_heads, cfg.head_dim)[b]
         ref = num.act(O.attention_one_sequence(qb, k[b, :L + R].cpu().double(), v[b, :L + R].cpu().double(), L, num))
         diff = (got[b] - ref).abs()
-        assert torch.all(diff <= ref.abs() * 2.0 ** -7 + 1e-6), (b, diff.max())
+        # Outputs are bf16: most elements are identical.  A probability whose
+        # fp32 and fp64 evaluations straddle a bf16 rounding boundary moves a
+        # whole output row by about 2^-8 * p_j / sum(p) * |v_j|, so the bound is
+        # absolute (values are O(1)), not one ulp of each element.
+        assert diff.max().item() <= 4e-3, (b, diff.max())
         assert (diff == 0).double().mean().item() > 0.97, (b, (diff == 0).double().mean().item())
 
 
