@@ -43,7 +43,7 @@ GemmPlan plan_gemm(int M, int N, int Kd, bool allow_split, bool need_even_nt) {
     while (nt > 1 && (ntiles + 4 * nt - 1) / (4 * nt) * (allow_split ? 4 : 1) < g_target_wgs) nt /= 2;
   }
   if (need_even_nt && nt < 2) nt = 2;
-  if (p.mt == 9 && nt > 2) nt = 2;  // accumulators of 9 x 4 tiles exceed the register file
+  if (p.mt >= 5 && nt > 2) nt = 2;  // accumulators plus the prefetch ring exceed the register file
   p.nt = nt;
   int nblocks = (ntiles + 4 * nt - 1) / (4 * nt);
   int splits = 1;

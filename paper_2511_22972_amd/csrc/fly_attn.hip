@@ -62,14 +62,16 @@ __global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages
   constexpr int nthreads = NW * 64;
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: scalar branches
   const int g = lane >> 4, c16 = lane & 15;
   const int split = blockIdx.x, pair = blockIdx.y, nsplit = gridDim.x;
   const int b = pair / Hkv, kvh = pair % Hkv;
   const int G = Hq / Hkv;
   const int R = G * (K + 1);
   const int L = kv_len[b];
-  const int total = L + K + 1;  // keys visible to the last query
+  int total = L + K + 1;  // keys visible to the last query
+  if (total > capacity) total = capacity;  // the host checks this bound; never read past the slab
   const int key_begin = split * chunk_keys;
   int key_end = key_begin + chunk_keys;
   if (key_end > total) key_end = total;
@@ -87,12 +89,15 @@ __global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
     int r = (wave * QTW + t) * 16 + c16;
     bool ok = r < R;
     qrow[t] = ok ? r : -1;
-    int i = ok ? r / G : 0, gq = ok ? r % G : 0;
+    int rc = ok ? r : R - 1;  // clamp: the load is unconditional, the value is masked
+    int i = rc / G, gq = rc % G;
     qlimit[t] = ok ? L + i + 1 : 0;
     const bf16_t* qp = q + ((int64_t)(b * (K + 1) + i) * Hq + kvh * G + gq) * ATT_HD;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-      qf[t][kk] = ok ? *(const u32x4*)(qp + 32 * kk + 8 * g) : u32x4{0u, 0u, 0u, 0u};
+    for (int kk = 0; kk < 4; ++kk) {
+      u32x4 v = *(const u32x4*)(qp + 32 * kk + 8 * g);
+      qf[t][kk] = ok ? v : u32x4{0u, 0u, 0u, 0u};
+    }
   }
 
   f32x4 oacc[QTW][8];  // O^T[hd = 16*ht + 4g + r][row c16]
@@ -109,56 +114,51 @@ __global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
   // 16 bytes per thread per item; items [0, 1024) are K, [1024, 2048) are V.
   constexpr int ITEMS = (ATT_KC * ATT_HD * 2 * 2) / 16;  // 2048
   constexpr int MAX_PER_THREAD = ITEMS / nthreads;       // 8 (four waves) or 4 (eight waves)
-  constexpr int per_thread = MAX_PER_THREAD;
   u32x4 stg[MAX_PER_THREAD];
 
+  // Loads are unconditional and branch-free so that all of a stage's loads are
+  // in flight together: a stage starts at a multiple of 64 below key_end and the
+  // capacity is a multiple of 64, so rows kstart..kstart+63 exist in the slab.
+  // Rows / columns at or past key_end hold whatever the allocation held
+  // (possibly NaN patterns; 0 * NaN would poison the sums): they are zeroed
+  // when the stage is written to LDS, which only the last stage needs.
   auto load_stage = [&](int kstart) {
 #pragma unroll
     for (int it = 0; it < MAX_PER_THREAD; ++it) {
-      if (it < per_thread) {
-        int item = it * nthreads + tid;
-        u32x4 v = u32x4{0u, 0u, 0u, 0u};
-        if (item < ITEMS / 2) {
-          int key = item >> 4, piece = item & 15;
-          int gk = kstart + key;
-          if (gk < key_end) v = *(const u32x4*)(kbase + (int64_t)gk * ATT_HD + piece * 8);
-        } else {
-          int it2 = item - ITEMS / 2;
-          int row = it2 >> 3, piece = it2 & 7;
-          int gk = kstart + piece * 8;  // 8 keys per 16-byte piece
-          // capacity is a multiple of 64 and kstart a multiple of 64: the piece lies inside the row
-          if (gk < key_end) {
-            v = *(const u32x4*)(vbase + (int64_t)row * capacity + gk);
-            // cache columns past the last valid key hold whatever the allocation
-            // held (possibly NaN patterns); zero them, 0 * NaN would poison the sum
-            int nvalid = key_end - gk;
-            if (nvalid < 8) {
-#pragma unroll
-              for (int w = 0; w < 4; ++w) {
-                uint32_t keep = (2 * w < nvalid ? 0xFFFFu : 0u) | (2 * w + 1 < nvalid ? 0xFFFF0000u : 0u);
-                v[w] &= keep;
-              }
-            }
-          }
-        }
-        stg[it] = v;
+      const int item = it * nthreads + tid;
+      if (it < MAX_PER_THREAD / 2) {  // K half (compile-time split)
+        int key = item >> 4, piece = item & 15;
+        stg[it] = *(const u32x4*)(kbase + (int64_t)(kstart + key) * ATT_HD + piece * 8);
+      } else {
+        int it2 = item - ITEMS / 2;
+        int row = it2 >> 3, piece = it2 & 7;
+        stg[it] = *(const u32x4*)(vbase + (int64_t)row * capacity + kstart + piece * 8);
       }
     }
   };
-  auto store_stage = [&](int stage) {
+  auto store_stage = [&](int stage, int kstart) {
     unsigned char* base = smem + stage * ATT_STAGE_BYTES;
+    const bool tail = kstart + ATT_KC > key_end;  // workgroup-uniform
 #pragma unroll
     for (int it = 0; it < MAX_PER_THREAD; ++it) {
-      if (it < per_thread) {
-        int item = it * nthreads + tid;
-        if (item < ITEMS / 2) {
-          int key = item >> 4, piece = item & 15;
-          *(u32x4*)(base + key * ATT_KROW + ATT_KSWZ(key, piece)) = stg[it];
-        } else {
-          int it2 = item - ITEMS / 2;
-          int row = it2 >> 3, piece = it2 & 7;
-          *(u32x4*)(base + ATT_KC * ATT_KROW + row * ATT_VROW + ATT_VSWZ(row, piece)) = stg[it];
+      const int item = it * nthreads + tid;
+      u32x4 v = stg[it];
+      if (it < MAX_PER_THREAD / 2) {
+        int key = item >> 4, piece = item & 15;
+        if (tail && kstart + key >= key_end) v = u32x4{0u, 0u, 0u, 0u};
+        *(u32x4*)(base + key * ATT_KROW + ATT_KSWZ(key, piece)) = v;
+      } else {
+        int it2 = item - ITEMS / 2;
+        int row = it2 >> 3, piece = it2 & 7;
+        if (tail) {
+          int nvalid = key_end - (kstart + piece * 8);  // valid keys in this 8-key piece
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            uint32_t keep = (2 * w < nvalid ? 0xFFFFu : 0u) | (2 * w + 1 < nvalid ? 0xFFFF0000u : 0u);
+            v[w] &= keep;
+          }
         }
+        *(u32x4*)(base + ATT_KC * ATT_KROW + row * ATT_VROW + ATT_VSWZ(row, piece)) = v;
       }
     }
   };
@@ -166,7 +166,7 @@ __global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
   const int nstages = key_end > key_begin ? (key_end - key_begin + ATT_KC - 1) / ATT_KC : 0;
   if (nstages > 0) {
     load_stage(key_begin);
-    store_stage(0);
+    store_stage(0, key_begin);
   }
   __syncthreads();
 
@@ -214,17 +214,17 @@ __global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
       float mnew = fmaxf(mrun[t], ceilf(mx));
       // rows with nothing visible yet keep n = -inf; avoid inf - inf
       float msafe = (mnew == -INFINITY) ? 0.f : mnew;
-      float corr = exp2f(mrun[t] - msafe);  // exact power of two (0 when mrun = -inf)
+      float corr = fast_exp2(mrun[t] - msafe);  // exact power of two (0 when mrun = -inf)
       mrun[t] = mnew;
       float lsum = 0.f;
       uint32_t pb[4][2];  // bf16 pairs: P[key 16*kt + 4g + {0,1}], {2,3}
 #pragma unroll
       for (int kt = 0; kt < 4; ++kt) {
-        float p0 = exp2f(sacc[kt][0] - msafe), p1 = exp2f(sacc[kt][1] - msafe);
-        float p2 = exp2f(sacc[kt][2] - msafe), p3 = exp2f(sacc[kt][3] - msafe);
+        float p0 = fast_exp2(sacc[kt][0] - msafe), p1 = fast_exp2(sacc[kt][1] - msafe);
+        float p2 = fast_exp2(sacc[kt][2] - msafe), p3 = fast_exp2(sacc[kt][3] - msafe);
         lsum += (p0 + p1) + (p2 + p3);
-        pb[kt][0] = pack_bf2(p0, p1);
-        pb[kt][1] = pack_bf2(p2, p3);
+        pb[kt][0] = pack_bf2_hw(p0, p1);
+        pb[kt][1] = pack_bf2_hw(p2, p3);
       }
       lrun[t] = lrun[t] * corr + lsum;
 #pragma unroll
@@ -256,7 +256,7 @@ __global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
         }
       }
     }
-    if (sidx + 1 < nstages) store_stage(stage ^ 1);
+    if (sidx + 1 < nstages) store_stage(stage ^ 1, kstart + ATT_KC);
     __syncthreads();
   }
 
@@ -300,7 +300,7 @@ __global__ __launch_bounds__(ATT_HD) void attention_combine_kernel(const float* 
     float ms = sb[(int64_t)R * ATT_HD + r];
     float ls = sb[(int64_t)R * ATT_HD + R + r];
     if (ls > 0.f) {
-      float w = exp2f(ms - mx);  // integer exponents: an exact power of two
+      float w = fast_exp2(ms - mx);  // integer exponents: an exact power of two
       num += sb[(int64_t)r * ATT_HD + e] * w;
       den += ls * w;
     }

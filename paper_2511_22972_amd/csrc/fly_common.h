@@ -23,6 +23,17 @@ __device__ __forceinline__ uint32_t pack_bf2(float lo, float hi) {
   return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
 }
 
+// Same rounding through the packed hardware conversion (v_cvt_pk_bf16_f32, RNE).
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+__device__ __forceinline__ uint32_t pack_bf2_hw(float lo, float hi) {
+  bf16x2_t v;
+  v.x = (__bf16)lo;
+  v.y = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, v);
+}
+// 2^x through the hardware transcendental (1 ulp; exact for integer x; 0 for -inf).
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 template <typename T> struct Act;
 template <> struct Act<float> {
   static __device__ __forceinline__ float ld(const float* p) { return *p; }

@@ -80,16 +80,18 @@ struct GemmRegs {
 };
 
 // Issue the global loads of one k-chunk: NT x GEMM_KS weight tiles for this wave.
-template <int NT>
-__device__ __forceinline__ void load_weight_chunk(u32x4 (&a)[NT][GEMM_KS], const u32x4* wbase,
-                                                  const bool (&tile_ok)[NT], int64_t strip_stride,
+// Unchecked form: every k-step of the chunk exists (branch-free, so all loads
+// of the chunk are in flight together).  Checked form (ragged last chunk):
+// k-steps at or past ks_end are replaced by zeros.
+template <int NT, bool CHECK>
+__device__ __forceinline__ void load_weight_chunk(u32x4 (&a)[NT][GEMM_KS], const u32x4* const (&wstrip)[NT],
                                                   int ks0, int ks_end, int lane) {
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
 #pragma unroll
     for (int s = 0; s < GEMM_KS; ++s) {
-      if (tile_ok[j] && ks0 + s < ks_end) {
-        a[j][s] = __builtin_nontemporal_load(wbase + j * strip_stride + (int64_t)(ks0 + s) * 64 + lane);
+      if (!CHECK || ks0 + s < ks_end) {
+        a[j][s] = __builtin_nontemporal_load(wstrip[j] + (int64_t)(ks0 + s) * 64 + lane);
       } else {
         a[j][s] = u32x4{0u, 0u, 0u, 0u};
       }
@@ -106,7 +108,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
   __shared__ u32x4 xs[2][GEMM_KS][MT][64];
 
   const int lane = threadIdx.x & 63;
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // scalar: uniform branches
   const int g = lane >> 4, c16 = lane & 15;
   const int ksteps_total = Kd / 32;
   const int nchunks_total = (ksteps_total + GEMM_KS - 1) / GEMM_KS;
@@ -114,15 +116,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
   int chunk_end = chunk_begin + chunks_per_split;
   if (chunk_end > nchunks_total) chunk_end = nchunks_total;
   const int ks_end = min(chunk_end * GEMM_KS, ksteps_total);
+  // chunks [chunk_begin, full_end) are complete; at most one ragged chunk follows
+  const int full_end = (ks_end == chunk_end * GEMM_KS) ? chunk_end : chunk_end - 1;
   const int mrow0 = blockIdx.z * (MT * 16);
   const int ntiles = N / 16;
   const int tn0 = (blockIdx.x * 4 + wave) * NT;
 
+  // Column strips of this wave.  A strip past the last tile (ragged last
+  // workgroup) is clamped to the last tile: it is loaded and multiplied like the
+  // others, and simply not stored.
   bool tile_ok[NT];
-#pragma unroll
-  for (int j = 0; j < NT; ++j) tile_ok[j] = (tn0 + j) < ntiles;
+  const u32x4* wstrip[NT];
   const int64_t strip_stride = (int64_t)ksteps_total * 64;  // u32x4 units per column strip
-  const u32x4* wbase = Wp + (int64_t)tn0 * strip_stride;
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    tile_ok[j] = (tn0 + j) < ntiles;
+    wstrip[j] = Wp + (int64_t)min(tn0 + j, ntiles - 1) * strip_stride;
+  }
 
   f32x4 acc[NT][MT];
 #pragma unroll
@@ -130,18 +140,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
 #pragma unroll
     for (int t = 0; t < MT; ++t) acc[j][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Activation fragments this wave stages per chunk: f = wave, wave+4, ... < KS*MT.
-  constexpr int NFRAG = (GEMM_KS * MT + 3) / 4;
-  u32x4 xf[NFRAG];
-  auto load_x = [&](int chunk) {
+  // Activation fragments this wave stages per chunk: f = wave + 4i, i < MT
+  // (k-step f / MT, row tile f % MT).  Rows past M are clamped to row M-1: they
+  // only feed output rows that are never stored.
+  u32x4 xf[MT];
+  const bf16_t* xrow[MT];
 #pragma unroll
-    for (int i = 0; i < NFRAG; ++i) {
-      int f = wave + 4 * i;
-      int s = f / MT, t = f % MT;
-      int row = mrow0 + t * 16 + c16;
-      int kstep = chunk * GEMM_KS + s;
-      if (f < GEMM_KS * MT && row < M && kstep < ks_end) {
-        xf[i] = *(const u32x4*)(X + (int64_t)row * Kd + kstep * 32 + 8 * g);
+  for (int i = 0; i < MT; ++i) {
+    int f = wave + 4 * i;
+    int row = min(mrow0 + (f % MT) * 16 + c16, M - 1);
+    xrow[i] = X + (int64_t)row * Kd + (f / MT) * 32 + 8 * g;
+  }
+  auto load_x = [&](int chunk, bool check) {
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      int kstep = chunk * GEMM_KS + (wave + 4 * i) / MT;
+      if (!check || kstep < ks_end) {
+        xf[i] = *(const u32x4*)(xrow[i] + (int64_t)chunk * (GEMM_KS * 32));
       } else {
         xf[i] = u32x4{0u, 0u, 0u, 0u};
       }
@@ -149,13 +164,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
   };
   auto store_x = [&](int stage) {
 #pragma unroll
-    for (int i = 0; i < NFRAG; ++i) {
+    for (int i = 0; i < MT; ++i) {
       int f = wave + 4 * i;
-      if (f < GEMM_KS * MT) xs[stage][f / MT][f % MT][lane] = xf[i];
+      xs[stage][f / MT][f % MT][lane] = xf[i];
     }
   };
-
-  u32x4 a0[NT][GEMM_KS], a1[NT][GEMM_KS];
 
   auto compute = [&](const u32x4 (&a)[NT][GEMM_KS], int stage) {
 #pragma unroll
@@ -173,34 +186,65 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     }
   };
 
+  // Software pipeline over k-chunks with a ring of three weight buffers: while
+  // chunk c is multiplied, the weights of chunks c+1 and c+2 are in flight.
+  // The activation loads of chunk c+1 are issued BEFORE the weight loads of
+  // chunk c+2, so that writing them to LDS at the end of the step waits only
+  // for them (loads retire in order) and leaves the weight loads in flight.
+  u32x4 a0[NT][GEMM_KS], a1[NT][GEMM_KS], a2[NT][GEMM_KS];
+  int stage = 0;
+
+#define FLY_GEMM_STEP(CUR, NXT2, c)                                                     \
+  {                                                                                     \
+    const int c_ = (c);                                                                 \
+    if (c_ + 1 < chunk_end) load_x(c_ + 1, c_ + 1 >= full_end);                          \
+    if (c_ + 2 < full_end) load_weight_chunk<NT, false>(NXT2, wstrip, (c_ + 2) * GEMM_KS, ks_end, lane); \
+    else if (c_ + 2 < chunk_end) load_weight_chunk<NT, true>(NXT2, wstrip, (c_ + 2) * GEMM_KS, ks_end, lane); \
+    compute(CUR, stage);                                                                \
+    if (c_ + 1 < chunk_end) store_x(stage ^ 1);                                         \
+    __syncthreads();                                                                    \
+    stage ^= 1;                                                                         \
+  }
+
+#define FLY_GEMM_STEP_FAST(CUR, NXT2, c)                                                \
+  {                                                                                     \
+    load_x((c) + 1, false);                                                             \
+    load_weight_chunk<NT, false>(NXT2, wstrip, ((c) + 2) * GEMM_KS, ks_end, lane);      \
+    compute(CUR, stage);                                                                \
+    store_x(stage ^ 1);                                                                 \
+    __syncthreads();                                                                    \
+    stage ^= 1;                                                                         \
+  }
+
   if (chunk_begin < chunk_end) {
-    load_weight_chunk<NT>(a0, wbase, tile_ok, strip_stride, chunk_begin * GEMM_KS, ks_end, lane);
-    load_x(chunk_begin);
+    load_x(chunk_begin, chunk_begin >= full_end);
+    if (chunk_begin < full_end) load_weight_chunk<NT, false>(a0, wstrip, chunk_begin * GEMM_KS, ks_end, lane);
+    else load_weight_chunk<NT, true>(a0, wstrip, chunk_begin * GEMM_KS, ks_end, lane);
+    if (chunk_begin + 1 < full_end) load_weight_chunk<NT, false>(a1, wstrip, (chunk_begin + 1) * GEMM_KS, ks_end, lane);
+    else if (chunk_begin + 1 < chunk_end) load_weight_chunk<NT, true>(a1, wstrip, (chunk_begin + 1) * GEMM_KS, ks_end, lane);
     store_x(0);
     __syncthreads();
-    int stage = 0;
-    for (int c = chunk_begin; c < chunk_end; c += 2) {
-      // even half: compute from a0, prefetch into a1
-      if (c + 1 < chunk_end) {
-        load_weight_chunk<NT>(a1, wbase, tile_ok, strip_stride, (c + 1) * GEMM_KS, ks_end, lane);
-        load_x(c + 1);
-      }
-      compute(a0, stage);
-      if (c + 1 < chunk_end) store_x(stage ^ 1);
-      __syncthreads();
-      stage ^= 1;
+    int c = chunk_begin;
+    // Steady state: three branch-free steps per trip (the ring returns to a0),
+    // taken while every chunk touched is complete.  Without conditionals in the
+    // body the wait counts before each multiply cover only the buffer in use.
+    while (c + 4 < full_end) {
+      FLY_GEMM_STEP_FAST(a0, a2, c);
+      FLY_GEMM_STEP_FAST(a1, a0, c + 1);
+      FLY_GEMM_STEP_FAST(a2, a1, c + 2);
+      c += 3;
+    }
+    // Tail: the last few chunks, with bounds checks (a0 holds chunk c, a1 chunk c+1).
+    for (; c < chunk_end; c += 3) {
+      FLY_GEMM_STEP(a0, a2, c);
       if (c + 1 >= chunk_end) break;
-      // odd half: compute from a1, prefetch into a0
-      if (c + 2 < chunk_end) {
-        load_weight_chunk<NT>(a0, wbase, tile_ok, strip_stride, (c + 2) * GEMM_KS, ks_end, lane);
-        load_x(c + 2);
-      }
-      compute(a1, stage);
-      if (c + 2 < chunk_end) store_x(stage ^ 1);
-      __syncthreads();
-      stage ^= 1;
+      FLY_GEMM_STEP(a1, a0, c + 1);
+      if (c + 2 >= chunk_end) break;
+      FLY_GEMM_STEP(a2, a1, c + 2);
     }
   }
+#undef FLY_GEMM_STEP_FAST
+#undef FLY_GEMM_STEP
 
   // ---- epilogues.  Lane holds out^T[n = 16*tile + 4g + r][m = 16t + c16], r = 0..3.
   if constexpr (EPI == EPI_PARTIAL) {
@@ -320,8 +364,8 @@ static hipError_t launch_gemm_mt(const bf16_t* X, const bf16_t* Wp, void* out,
     case 1: return launch_gemm_mt_nt<MT, 1>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
     case 2: return launch_gemm_mt_nt<MT, 2>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
     case 4:
-      // nine row tiles times four column tiles of accumulators do not fit the register file
-      if constexpr (MT <= 5) return launch_gemm_mt_nt<MT, 4>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+      // five or nine row tiles times four column tiles plus the prefetch ring do not fit the register file
+      if constexpr (MT <= 3) return launch_gemm_mt_nt<MT, 4>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
       else return hipErrorInvalidValue;
   }
   return hipErrorInvalidValue;

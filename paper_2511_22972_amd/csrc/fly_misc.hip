@@ -32,15 +32,17 @@ hipError_t launch_embed(const int32_t* tokens, const void* embed, int dtype, flo
 // One workgroup per row.  The split-K partial sums are added in split order,
 // so the result does not depend on scheduling.
 // ---------------------------------------------------------------------------
+#define RRN_THREADS 1024
 template <typename AT>
-__global__ __launch_bounds__(256) void reduce_residual_norm_kernel(
+__global__ __launch_bounds__(RRN_THREADS) void reduce_residual_norm_kernel(
     float* __restrict__ x, const float* __restrict__ partial, int splits, const AT* __restrict__ gain,
     AT* __restrict__ xn, int M, int d, float eps) {
-  __shared__ float wsum[4];
+  __shared__ float wsum[RRN_THREADS / 64];
   const int m = blockIdx.x;
   float* xr = x + (int64_t)m * d;
   float ss = 0.f;
-  for (int i = threadIdx.x * 4; i < d; i += 256 * 4) {
+  // Only M rows exist, so the row is spread over 16 waves to keep enough loads in flight.
+  for (int i = threadIdx.x * 4; i < d; i += RRN_THREADS * 4) {
     f32x4 v = *(f32x4*)(xr + i);
     for (int s = 0; s < splits; ++s) {
       f32x4 p = *(const f32x4*)(partial + ((int64_t)s * M + m) * d + i);
@@ -53,10 +55,12 @@ __global__ __launch_bounds__(256) void reduce_residual_norm_kernel(
   ss = wave_sum(ss);
   if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = ss;
   __syncthreads();
-  float tot = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < RRN_THREADS / 64; ++w) tot += wsum[w];
   float inv = 1.0f / sqrtf(tot / (float)d + eps);
   AT* o = xn + (int64_t)m * d;
-  for (int i = threadIdx.x * 4; i < d; i += 256 * 4) {
+  for (int i = threadIdx.x * 4; i < d; i += RRN_THREADS * 4) {
     f32x4 v = *(f32x4*)(xr + i);
 #pragma unroll
     for (int e = 0; e < 4; ++e) Act<AT>::st(o + i + e, v[e] * inv * Act<AT>::ld(gain + i + e));
@@ -67,10 +71,10 @@ hipError_t launch_reduce_residual_norm(float* x, const float* partial, int split
                                        void* xn, int dtype, int M, int d, float eps, hipStream_t st) {
   if (d % 4 != 0) return hipErrorInvalidValue;
   if (dtype == FLY_BF16)
-    hipLaunchKernelGGL(reduce_residual_norm_kernel<bf16_t>, dim3(M), dim3(256), 0, st, x, partial,
+    hipLaunchKernelGGL(reduce_residual_norm_kernel<bf16_t>, dim3(M), dim3(RRN_THREADS), 0, st, x, partial,
                        splits, (const bf16_t*)gain, (bf16_t*)xn, M, d, eps);
   else
-    hipLaunchKernelGGL(reduce_residual_norm_kernel<float>, dim3(M), dim3(256), 0, st, x, partial,
+    hipLaunchKernelGGL(reduce_residual_norm_kernel<float>, dim3(M), dim3(RRN_THREADS), 0, st, x, partial,
                        splits, (const float*)gain, (float*)xn, M, d, eps);
   return hipGetLastError();
 }
