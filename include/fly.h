@@ -126,7 +126,9 @@ const char* fly_strerror(fly_status s);
  * Launch-shape knobs for experiments (process-wide, not thread-safe):
  *   "gemm_nt"      16-column weight tiles per wavefront: 1, 2, 4; 0 = automatic
  *   "gemm_splits"  split-K factor of the projections: 1..16; 0 = automatic
- *   "target_wgs"   workgroups a launch aims for (default 512)
+ *   "attn_splits"  cache splits per (sequence, KV head): 1..256; 0 = automatic
+ *   "attn_qtw"     16-row query tiles per wavefront: 1..3; 0 = automatic
+ *   "target_wgs"   workgroups a launch aims for (default 256, one per compute unit)
  * Workspace sizes depend on them: query again after a change.
  */
 fly_status fly_set_tuning(const char* key, int32_t value);
@@ -207,6 +209,18 @@ fly_status fly_lmhead_entropy_argmax(const void* hidden, const void* w_lm, const
 fly_status fly_accept(const int32_t* draft, const int32_t* tgt_argmax, const float* h_norm,
                       int32_t B, int32_t K, float theta, int32_t W, int32_t* accept_len,
                       int32_t* next_token, int32_t* n_loose, fly_stream stream);
+
+/*
+ * A plain projection as the layers run it (q/k/v, output and down projections;
+ * exposed for per-kernel timing and checks): split-K partial sums
+ *   partial[s, m, n] = sum over the k-range of split s of xn[m, k] * W[k, n]
+ *   xn       [device] [M, Kd] model dtype;  w [device] packed [Kd, N]
+ *   partial  [device] float [splits, M, N]; partial_bytes is its size, at least
+ *            16*M*N*4 is always enough; *splits_out [host] receives the split count
+ */
+fly_status fly_proj_partial(const void* xn, const void* w, float* partial, int32_t M, int32_t N,
+                            int32_t Kd, int32_t dtype, int32_t* splits_out, size_t partial_bytes,
+                            fly_stream stream);
 
 /*
  * Gate/up projection with the SwiGLU product fused into the GEMM epilogue

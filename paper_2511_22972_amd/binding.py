@@ -22,7 +22,7 @@ FLY_F32, FLY_BF16 = 0, 1
 EXPORTS = [
     "fly_strerror", "fly_set_tuning", "fly_packed_weight_bytes", "fly_pack_weight",
     "fly_workspace_bytes", "fly_lmhead_workspace_bytes", "fly_verify_block", "fly_decoder_layers",
-    "fly_lmhead_entropy_argmax", "fly_accept", "fly_attention", "fly_gateup_swiglu",
+    "fly_lmhead_entropy_argmax", "fly_accept", "fly_attention", "fly_gateup_swiglu", "fly_proj_partial",
 ]
 
 
@@ -93,6 +93,8 @@ def _load() -> C.CDLL:
                                   C.c_void_p]
     lib.fly_gateup_swiglu.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                       C.c_int32, C.c_int32, C.c_void_p]
+    lib.fly_proj_partial.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                     C.c_int32, C.POINTER(C.c_int32), C.c_size_t, C.c_void_p]
     for name in EXPORTS:
         if name != "fly_strerror":
             getattr(lib, name).restype = C.c_int
@@ -332,6 +334,15 @@ def fly_gateup_swiglu(xn: torch.Tensor, w_gateup_packed: torch.Tensor, a: torch.
     F = a.shape[1]
     _check(lib.fly_gateup_swiglu(_ptr(xn), _ptr(w_gateup_packed), _ptr(a), M, d, F,
                                  dtype_code(xn.dtype), _stream()), "fly_gateup_swiglu")
+
+
+def fly_proj_partial(xn: torch.Tensor, w_packed: torch.Tensor, partial: torch.Tensor, N: int) -> int:
+    """Returns the number of split-K partials written to `partial` (float32, flat)."""
+    M, Kd = xn.shape
+    splits = C.c_int32(0)
+    _check(lib.fly_proj_partial(_ptr(xn), _ptr(w_packed), _ptr(partial), M, N, Kd, dtype_code(xn.dtype),
+                                C.byref(splits), partial.numel() * 4, _stream()), "fly_proj_partial")
+    return splits.value
 
 
 def alloc_workspace(nbytes: int, device="cuda") -> torch.Tensor:

@@ -11,7 +11,7 @@ namespace {
 // --- tuning knobs (0 = automatic); set through fly_set_tuning ---------------
 int g_force_nt = 0;
 int g_force_splits = 0;
-int g_target_wgs = 512;
+int g_target_wgs = 256;
 
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 
@@ -27,42 +27,50 @@ int pick_mt(int rows) {
   return 9;
 }
 
-// Plan of one bf16 GEMM: enough workgroups to fill 256 compute units twice,
-// split-K only when the output is too narrow to do that alone.
+// Plan of one bf16 GEMM.  Measured on MI355X: the kernel streams best with
+// about one workgroup per compute unit (256), each wave holding as many column
+// strips as the register file allows (4 for up to 48 rows, else 2), so that
+// roughly 128 KiB of weight loads are in flight per compute unit.  Narrow
+// outputs reach that workgroup count by split-K; when four-strip waves would
+// need eight or more splits, two-strip waves with half the splits write less
+// partial-sum traffic and win.
+int splits_for(int nblocks, int nchunks) {
+  int s = (g_target_wgs + nblocks / 2) / nblocks;  // round to nearest
+  int max_splits = nchunks / 4;                     // at least four 128-wide chunks per split
+  if (max_splits < 1) max_splits = 1;
+  if (s > max_splits) s = max_splits;
+  if (s > 16) s = 16;
+  if (s < 1) s = 1;
+  int cps = (nchunks + s - 1) / s;                  // drop empty trailing splits
+  return (nchunks + cps - 1) / cps;
+}
+
 GemmPlan plan_gemm(int M, int N, int Kd, bool allow_split, bool need_even_nt) {
   GemmPlan p;
   p.mblocks = (M + 143) / 144;
   p.mt = p.mblocks > 1 ? 9 : pick_mt(M);
-  int ntiles = N / 16;
-  int nchunks = (Kd / 32 + 3) / 4;
-  int nt = 4;
+  const int ntiles = N / 16;
+  const int nchunks = (Kd / 32 + 3) / 4;
+  const int nt_max = p.mt <= 3 ? 4 : 2;  // accumulators plus the prefetch ring must fit the register file
+  int nt = nt_max;
+  auto blocks = [&](int t) { return (ntiles + 4 * t - 1) / (4 * t); };
   if (g_force_nt) {
     nt = g_force_nt;
+  } else if (allow_split) {
+    if (nt == 4 && splits_for(blocks(4), nchunks) >= 8 && splits_for(blocks(2), nchunks) <= 4) nt = 2;
   } else {
-    // widest wave tile that still yields the wanted number of workgroups
-    while (nt > 1 && (ntiles + 4 * nt - 1) / (4 * nt) * (allow_split ? 4 : 1) < g_target_wgs) nt /= 2;
+    // no split-K possible: narrow the wave tile until the launch has enough workgroups
+    while (nt > 1 && blocks(nt) < g_target_wgs * 3 / 4) nt /= 2;
   }
+  if (nt > nt_max) nt = nt_max;
   if (need_even_nt && nt < 2) nt = 2;
-  if (p.mt >= 5 && nt > 2) nt = 2;  // accumulators plus the prefetch ring exceed the register file
   p.nt = nt;
-  int nblocks = (ntiles + 4 * nt - 1) / (4 * nt);
-  int splits = 1;
-  if (allow_split) {
-    if (g_force_splits) {
-      splits = g_force_splits;
-    } else {
-      splits = (g_target_wgs + nblocks - 1) / nblocks;
-    }
-    int max_splits = nchunks / 4;  // at least four 128-wide chunks per split
-    if (max_splits < 1) max_splits = 1;
-    if (splits > max_splits) splits = max_splits;
-    if (splits > 16) splits = 16;
-    if (splits < 1) splits = 1;
-    // drop empty trailing splits
-    int cps = (nchunks + splits - 1) / splits;
-    splits = (nchunks + cps - 1) / cps;
+  p.splits = 1;
+  if (allow_split) p.splits = g_force_splits ? g_force_splits : splits_for(blocks(nt), nchunks);
+  if (allow_split && g_force_splits) {
+    int cps = (nchunks + p.splits - 1) / p.splits;
+    p.splits = (nchunks + cps - 1) / cps;
   }
-  p.splits = splits;
   return p;
 }
 
@@ -298,6 +306,12 @@ fly_status fly_set_tuning(const char* key, int32_t value) {
   } else if (!strcmp(key, "gemm_splits")) {
     if (value < 0 || value > 16) return FLY_ERR_BAD_SHAPE;
     g_force_splits = value;
+  } else if (!strcmp(key, "attn_splits")) {
+    if (value < 0 || value > 256) return FLY_ERR_BAD_SHAPE;
+    g_attn_force_splits = value;
+  } else if (!strcmp(key, "attn_qtw")) {
+    if (value < 0 || value > 3) return FLY_ERR_BAD_SHAPE;
+    g_attn_force_qtw = value;
   } else if (!strcmp(key, "target_wgs")) {
     if (value < 1) return FLY_ERR_BAD_SHAPE;
     g_target_wgs = value;
@@ -439,6 +453,20 @@ fly_status fly_attention(const fly_model_desc* desc, const fly_kv_cache* kv, int
                                  (const float*)kv->v_layers[layer], kv->kv_len, (float*)o, B, K,
                                  desc->n_q_heads, desc->n_kv_heads, desc->head_dim, kv->capacity, st));
   return FLY_OK;
+}
+
+fly_status fly_proj_partial(const void* xn, const void* w, float* partial, int32_t M, int32_t N,
+                            int32_t Kd, int32_t dtype, int32_t* splits_out, size_t partial_bytes,
+                            fly_stream stream) {
+  if (!xn || !w || !partial || !splits_out) return FLY_ERR_NULL_POINTER;
+  if (dtype != FLY_F32 && dtype != FLY_BF16) return FLY_ERR_DTYPE;
+  if (M < 1 || N < 16 || N % 16 != 0 || Kd < 16) return FLY_ERR_BAD_SHAPE;
+  if (dtype == FLY_BF16 && Kd % 32 != 0) return FLY_ERR_BAD_SHAPE;
+  if (!aligned16(xn) || !aligned16(w) || !aligned16(partial)) return FLY_ERR_ALIGNMENT;
+  GemmPlan plan = dtype == FLY_BF16 ? plan_gemm(M, N, Kd, true, false) : GemmPlan{1, 1, 1, 1};
+  if (partial_bytes < (size_t)plan.splits * M * N * 4) return FLY_ERR_WORKSPACE;
+  *splits_out = plan.splits;
+  return run_gemm(dtype, xn, w, partial, nullptr, M, N, Kd, plan, EPI_PARTIAL, (hipStream_t)stream);
 }
 
 fly_status fly_gateup_swiglu(const void* xn, const void* w_gateup, void* a, int32_t M, int32_t d,

@@ -15,6 +15,7 @@
 #include "fly_common.h"
 
 #define ATT_HD 128
+#define ATT_MAX_SPLITS 256
 #define ATT_KC 64                      // keys per LDS stage
 #define ATT_KROW (ATT_HD * 2)           // bytes per key row in LDS
 #define ATT_VROW (ATT_KC * 2)           // bytes per V^T row in LDS
@@ -25,21 +26,27 @@
 #define ATT_KSWZ(key, piece) (((piece) ^ ((key) & 15)) * 16)
 #define ATT_VSWZ(row, piece) (((piece) ^ (((row) >> 1) & 7)) * 16)
 
+int g_attn_force_splits = 0;  // tuning knobs (0 = automatic)
+int g_attn_force_qtw = 0;
+
 AttnPlan plan_attention(int B, int K, int Hq, int Hkv, int max_total_len) {
   AttnPlan p;
   int G = Hq / Hkv;
   int R = G * (K + 1);
   int qt = (R + 15) / 16;
-  p.qtw = qt <= 4 ? 1 : (qt <= 10 ? 2 : 3);
+  p.qtw = qt <= 8 ? 1 : (qt <= 16 ? 2 : 3);  // up to eight waves per workgroup
+  if (g_attn_force_qtw) p.qtw = g_attn_force_qtw;
   p.nwaves = (qt + p.qtw - 1) / p.qtw;  // caller guarantees <= 8
   int pairs = B * Hkv;
   int chunks = (max_total_len + ATT_KC - 1) / ATT_KC;
   if (chunks < 1) chunks = 1;
-  // aim for about two workgroups per compute unit, at least two stages per split
-  int want = (512 + pairs - 1) / pairs;
+  // one workgroup per compute unit (the kernel's registers allow no more), at
+  // least two stages per split
+  int want = g_attn_force_splits ? g_attn_force_splits : (256 + pairs - 1) / pairs;
   int maxsplit = (chunks + 1) / 2;
   if (maxsplit < 1) maxsplit = 1;
   int ns = want < maxsplit ? want : maxsplit;
+  if (ns > ATT_MAX_SPLITS) ns = ATT_MAX_SPLITS;
   if (ns < 1) ns = 1;
   int cps = (chunks + ns - 1) / ns;
   p.chunk_keys = cps * ATT_KC;
@@ -114,7 +121,7 @@ __global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
   // 16 bytes per thread per item; items [0, 1024) are K, [1024, 2048) are V.
   constexpr int ITEMS = (ATT_KC * ATT_HD * 2 * 2) / 16;  // 2048
   constexpr int MAX_PER_THREAD = ITEMS / nthreads;       // 8 (four waves) or 4 (eight waves)
-  u32x4 stg[MAX_PER_THREAD];
+  u32x4 stgA[MAX_PER_THREAD], stgB[MAX_PER_THREAD];  // two stages in flight
 
   // Loads are unconditional and branch-free so that all of a stage's loads are
   // in flight together: a stage starts at a multiple of 64 below key_end and the
@@ -122,7 +129,7 @@ __global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
   // Rows / columns at or past key_end hold whatever the allocation held
   // (possibly NaN patterns; 0 * NaN would poison the sums): they are zeroed
   // when the stage is written to LDS, which only the last stage needs.
-  auto load_stage = [&](int kstart) {
+  auto load_stage = [&](u32x4 (&stg)[MAX_PER_THREAD], int kstart) {
 #pragma unroll
     for (int it = 0; it < MAX_PER_THREAD; ++it) {
       const int item = it * nthreads + tid;
@@ -136,7 +143,7 @@ __global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
       }
     }
   };
-  auto store_stage = [&](int stage, int kstart) {
+  auto store_stage = [&](const u32x4 (&stg)[MAX_PER_THREAD], int stage, int kstart) {
     unsigned char* base = smem + stage * ATT_STAGE_BYTES;
     const bool tail = kstart + ATT_KC > key_end;  // workgroup-uniform
 #pragma unroll
@@ -164,101 +171,158 @@ __global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
   };
 
   const int nstages = key_end > key_begin ? (key_end - key_begin + ATT_KC - 1) / ATT_KC : 0;
-  if (nstages > 0) {
-    load_stage(key_begin);
-    store_stage(0, key_begin);
-  }
-  __syncthreads();
 
-  for (int sidx = 0; sidx < nstages; ++sidx) {
-    const int kstart = key_begin + sidx * ATT_KC;
-    const int stage = sidx & 1;
-    if (sidx + 1 < nstages) load_stage(kstart + ATT_KC);
+  // One 64-key stage from LDS buffer `stage`, whose first key is kstart.
+  //
+  // Probabilities are formed relative to an INTEGER base-2 exponent n >= max s',
+  // s' = (q.k) * log2(e)/sqrt(hd), n = ceil of the running maximum: when the
+  // maximum grows, earlier terms are rescaled by an exact power of two, which
+  // commutes with the bf16 rounding of P.  The result is the same as rounding
+  // 2^(s' - n_final) once, independent of how the cache is chunked or split.
+  //
+  // The per-score vector work is what bounds this kernel once the loads are
+  // hidden, so it is kept minimal: the causal / tail mask is applied only in
+  // stages that reach past the prefix (uniform branch), the scale is folded
+  // into one fused multiply-add with the exponent, and the accumulators are
+  // rescaled only when some row's exponent actually changed.
+  const bool wave_has_rows = wave * QTW * 16 < R;
+  auto compute_stage = [&](int stage, int kstart) {
+    if (!wave_has_rows) return;  // this wave only helps with the loads
     const unsigned char* kb = smem + stage * ATT_STAGE_BYTES;
     const unsigned char* vb = kb + ATT_KC * ATT_KROW;
 
+    // S^T = K Q^T: 4 key tiles of 16; lane holds S[key = 16*kt + 4g + r][row c16].
+    // Each key fragment is read from LDS once and used for all of the wave's query tiles.
+    f32x4 sacc[QTW][4];
+#pragma unroll
+    for (int t = 0; t < QTW; ++t)
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt) sacc[t][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        u32x4 araw = *(const u32x4*)(kb + (kt * 16 + c16) * ATT_KROW + ATT_KSWZ(c16, 4 * kk + g));
+        bf16x8 a = __builtin_bit_cast(bf16x8, araw);
+#pragma unroll
+        for (int t = 0; t < QTW; ++t)
+          sacc[t][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, qf[t][kk]),
+                                                                sacc[t][kt], 0, 0, 0);
+      }
+    }
+
+    const bool need_mask = kstart + ATT_KC > L + 1;  // keys below L+1 are visible to every row
+    uint32_t pb[QTW][4][2];  // bf16 pairs: P[key 16*kt + 4g + {0,1}], {2,3}
 #pragma unroll
     for (int t = 0; t < QTW; ++t) {
-      if ((wave * QTW + t) * 16 >= R) continue;  // wave-uniform
-      // S^T tiles: 4 key tiles of 16; lane holds S[key = 16*kt + 4g + r][row c16]
-      f32x4 sacc[4];
+      if (need_mask) {
 #pragma unroll
-      for (int kt = 0; kt < 4; ++kt) {
-        sacc[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int kt = 0; kt < 4; ++kt)
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-          u32x4 araw = *(const u32x4*)(kb + (kt * 16 + c16) * ATT_KROW + ATT_KSWZ(c16, 4 * kk + g));
-          sacc[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, araw),
-                                                             __builtin_bit_cast(bf16x8, qf[t][kk]),
-                                                             sacc[kt], 0, 0, 0);
-        }
+          for (int r = 0; r < 4; ++r) {
+            int key = kstart + kt * 16 + 4 * g + r;
+            if (key >= qlimit[t]) sacc[t][kt][r] = -INFINITY;
+          }
       }
-      // Mask and move to the base-2 exponent domain: s' = (q.k) * scale * log2(e).
-      // Probabilities are formed relative to an INTEGER exponent n >= max s'
-      // (n = ceil of the running maximum): when the maximum grows, earlier
-      // terms are rescaled by an exact power of two, which commutes with the
-      // bf16 rounding of P.  The result is therefore the same as rounding
-      // 2^(s' - n_final) once, independent of how the cache is chunked or split.
       float mx = -INFINITY;
 #pragma unroll
       for (int kt = 0; kt < 4; ++kt)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          int key = kstart + kt * 16 + 4 * g + r;
-          float s = (key < qlimit[t]) ? sacc[kt][r] * scale : -INFINITY;
-          sacc[kt][r] = s;
-          mx = fmaxf(mx, s);
-        }
+        mx = fmaxf(mx, fmaxf(fmaxf(sacc[t][kt][0], sacc[t][kt][1]), fmaxf(sacc[t][kt][2], sacc[t][kt][3])));
       mx = fmaxf(mx, __shfl_xor(mx, 16, FLY_WAVE));
       mx = fmaxf(mx, __shfl_xor(mx, 32, FLY_WAVE));
-      float mnew = fmaxf(mrun[t], ceilf(mx));
+      const float mnew = fmaxf(mrun[t], ceilf(mx * scale));  // scale > 0: max commutes with it
       // rows with nothing visible yet keep n = -inf; avoid inf - inf
-      float msafe = (mnew == -INFINITY) ? 0.f : mnew;
-      float corr = fast_exp2(mrun[t] - msafe);  // exact power of two (0 when mrun = -inf)
-      mrun[t] = mnew;
+      const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+      if (__ballot(mnew != mrun[t]) != 0ull) {  // wave-uniform: some row's exponent grew
+        const float corr = fast_exp2(mrun[t] - msafe);  // exact power of two (0 when mrun = -inf)
+        lrun[t] *= corr;
+#pragma unroll
+        for (int ht = 0; ht < 8; ++ht) oacc[t][ht] *= corr;
+        mrun[t] = mnew;
+      }
       float lsum = 0.f;
-      uint32_t pb[4][2];  // bf16 pairs: P[key 16*kt + 4g + {0,1}], {2,3}
 #pragma unroll
       for (int kt = 0; kt < 4; ++kt) {
-        float p0 = fast_exp2(sacc[kt][0] - msafe), p1 = fast_exp2(sacc[kt][1] - msafe);
-        float p2 = fast_exp2(sacc[kt][2] - msafe), p3 = fast_exp2(sacc[kt][3] - msafe);
+        float p0 = fast_exp2(fmaf(sacc[t][kt][0], scale, -msafe));
+        float p1 = fast_exp2(fmaf(sacc[t][kt][1], scale, -msafe));
+        float p2 = fast_exp2(fmaf(sacc[t][kt][2], scale, -msafe));
+        float p3 = fast_exp2(fmaf(sacc[t][kt][3], scale, -msafe));
         lsum += (p0 + p1) + (p2 + p3);
-        pb[kt][0] = pack_bf2_hw(p0, p1);
-        pb[kt][1] = pack_bf2_hw(p2, p3);
+        pb[t][kt][0] = pack_bf2_hw(p0, p1);
+        pb[t][kt][1] = pack_bf2_hw(p2, p3);
       }
-      lrun[t] = lrun[t] * corr + lsum;
+      lrun[t] += lsum;
+    }
+
+    // O^T += V^T P^T.  k-step ks covers keys 32ks..32ks+31 with the operand
+    // index order (4g..4g+3 of tile 2ks, then 4g..4g+3 of tile 2ks+1); each V^T
+    // fragment is read once and used for all query tiles.
 #pragma unroll
-      for (int ht = 0; ht < 8; ++ht) oacc[t][ht] *= corr;
-      // O^T += V^T P^T.  k-step ks covers keys 32ks..32ks+31 with the operand
-      // index order (4g..4g+3 of tile 2ks, then 4g..4g+3 of tile 2ks+1).
+    for (int ks = 0; ks < 2; ++ks) {
+      bf16x8 bop[QTW];
 #pragma unroll
-      for (int ks = 0; ks < 2; ++ks) {
+      for (int t = 0; t < QTW; ++t) {
         u32x4 braw;
-        braw.x = pb[2 * ks][0];
-        braw.y = pb[2 * ks][1];
-        braw.z = pb[2 * ks + 1][0];
-        braw.w = pb[2 * ks + 1][1];
-        bf16x8 bop = __builtin_bit_cast(bf16x8, braw);
+        braw.x = pb[t][2 * ks][0];
+        braw.y = pb[t][2 * ks][1];
+        braw.z = pb[t][2 * ks + 1][0];
+        braw.w = pb[t][2 * ks + 1][1];
+        bop[t] = __builtin_bit_cast(bf16x8, braw);
+      }
 #pragma unroll
-        for (int ht = 0; ht < 8; ++ht) {
-          // keys 32ks + 4g .. +3 sit in piece 4ks + g/2 at byte 8(g&1); keys +16 two pieces on
-          const int vrow = ht * 16 + c16;
-          const unsigned char* vr = vb + vrow * ATT_VROW + 8 * (g & 1);
-          u32x2 lo = *(const u32x2*)(vr + ATT_VSWZ(vrow, 4 * ks + (g >> 1)));
-          u32x2 hi = *(const u32x2*)(vr + ATT_VSWZ(vrow, 4 * ks + (g >> 1) + 2));
-          u32x4 araw;
-          araw.x = lo.x;
-          araw.y = lo.y;
-          araw.z = hi.x;
-          araw.w = hi.y;
-          oacc[t][ht] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, araw), bop,
-                                                                oacc[t][ht], 0, 0, 0);
-        }
+      for (int ht = 0; ht < 8; ++ht) {
+        // keys 32ks + 4g .. +3 sit in piece 4ks + g/2 at byte 8(g&1); keys +16 two pieces on
+        const int vrow = ht * 16 + c16;
+        const unsigned char* vr = vb + vrow * ATT_VROW + 8 * (g & 1);
+        u32x2 lo = *(const u32x2*)(vr + ATT_VSWZ(vrow, 4 * ks + (g >> 1)));
+        u32x2 hi = *(const u32x2*)(vr + ATT_VSWZ(vrow, 4 * ks + (g >> 1) + 2));
+        u32x4 araw;
+        araw.x = lo.x;
+        araw.y = lo.y;
+        araw.z = hi.x;
+        araw.w = hi.y;
+        bf16x8 a = __builtin_bit_cast(bf16x8, araw);
+#pragma unroll
+        for (int t = 0; t < QTW; ++t)
+          oacc[t][ht] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bop[t], oacc[t][ht], 0, 0, 0);
       }
     }
-    if (sidx + 1 < nstages) store_stage(stage ^ 1, kstart + ATT_KC);
+  };
+
+  // Pipeline: while stage i is multiplied out of LDS, stage i+1 sits in
+  // registers waiting to be written to the other LDS buffer and stage i+2 is
+  // being loaded.  Register sets alternate (A, B), LDS buffers alternate (0, 1).
+  // The steady-state loop has no conditionals so that the waits before the LDS
+  // writes cover only the older of the two register sets.
+#define KST(i) (key_begin + (i) * ATT_KC)
+  if (nstages > 0) load_stage(stgA, KST(0));
+  if (nstages > 1) load_stage(stgB, KST(1));
+  if (nstages > 0) store_stage(stgA, 0, KST(0));
+  __syncthreads();
+  int sidx = 0;
+  while (sidx + 3 < nstages) {
+    load_stage(stgA, KST(sidx + 2));
+    compute_stage(0, KST(sidx));
+    store_stage(stgB, 1, KST(sidx + 1));
+    __syncthreads();
+    load_stage(stgB, KST(sidx + 3));
+    compute_stage(1, KST(sidx + 1));
+    store_stage(stgA, 0, KST(sidx + 2));
+    __syncthreads();
+    sidx += 2;
+  }
+  for (; sidx < nstages; sidx += 2) {  // tail: at most three stages, with checks
+    if (sidx + 2 < nstages) load_stage(stgA, KST(sidx + 2));
+    compute_stage(0, KST(sidx));
+    if (sidx + 1 < nstages) store_stage(stgB, 1, KST(sidx + 1));
+    __syncthreads();
+    if (sidx + 1 >= nstages) break;
+    if (sidx + 3 < nstages) load_stage(stgB, KST(sidx + 3));
+    compute_stage(1, KST(sidx + 1));
+    if (sidx + 2 < nstages) store_stage(stgA, 0, KST(sidx + 2));
     __syncthreads();
   }
+#undef KST
 
   // ---- write this split's partial: O [R, hd], m [R], l [R]
   float* obase = ws + ((int64_t)pair * nsplit + split) * (int64_t)R * (ATT_HD + 2);
@@ -287,23 +351,31 @@ __global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
 __global__ __launch_bounds__(ATT_HD) void attention_combine_kernel(const float* __restrict__ ws,
                                                                    bf16_t* __restrict__ o, int K,
                                                                    int Hq, int Hkv, int nsplit) {
+  __shared__ float wgt[ATT_MAX_SPLITS];  // 2^(n_s - n) per split, 0 for empty splits
+  __shared__ float lw[ATT_MAX_SPLITS];   // l_s * weight
   const int r = blockIdx.x, pair = blockIdx.y, e = threadIdx.x;
   const int b = pair / Hkv, kvh = pair % Hkv;
   const int G = Hq / Hkv, R = G * (K + 1);
   const float* base = ws + (int64_t)pair * nsplit * (int64_t)R * (ATT_HD + 2);
   const int64_t sstride = (int64_t)R * (ATT_HD + 2);
+  // every thread finds the largest exponent (the loads are the same for all
+  // threads and independent of each other)
   float mx = -INFINITY;
   for (int s = 0; s < nsplit; ++s) mx = fmaxf(mx, base[s * sstride + (int64_t)R * ATT_HD + r]);
+  for (int s = e; s < nsplit; s += ATT_HD) {
+    const float* sb = base + s * sstride + (int64_t)R * ATT_HD;
+    float ms = sb[r], ls = sb[R + r];
+    float w = ls > 0.f ? fast_exp2(ms - mx) : 0.f;  // integer exponents: an exact power of two
+    wgt[s] = w;
+    lw[s] = ls * w;
+  }
+  __syncthreads();
   float num = 0.f, den = 0.f;
+  // split order is fixed, so the sum does not depend on scheduling
+#pragma unroll 4
   for (int s = 0; s < nsplit; ++s) {
-    const float* sb = base + s * sstride;
-    float ms = sb[(int64_t)R * ATT_HD + r];
-    float ls = sb[(int64_t)R * ATT_HD + R + r];
-    if (ls > 0.f) {
-      float w = fast_exp2(ms - mx);  // integer exponents: an exact power of two
-      num += sb[(int64_t)r * ATT_HD + e] * w;
-      den += ls * w;
-    }
+    num = fmaf(base[s * sstride + (int64_t)r * ATT_HD + e], wgt[s], num);
+    den += lw[s];
   }
   const int i = r / G, gq = r % G;
   o[((int64_t)(b * (K + 1) + i) * Hq + kvh * G + gq) * ATT_HD + e] = f2bf(num / den);
@@ -316,6 +388,7 @@ hipError_t launch_attention_bf16(const bf16_t* q, const bf16_t* kcache, const bf
   if (hd != ATT_HD || Hq % Hkv != 0 || capacity % 64 != 0 || p.chunk_keys % ATT_KC != 0)
     return hipErrorInvalidValue;
   if (p.nwaves < 1 || p.nwaves > 8 || p.qtw < 1 || p.qtw > 3) return hipErrorInvalidValue;
+  if (p.nsplit < 1 || p.nsplit > ATT_MAX_SPLITS) return hipErrorInvalidValue;
   int G = Hq / Hkv, R = G * (K + 1);
   if (p.nwaves * p.qtw * 16 < R) return hipErrorInvalidValue;
   // the stage loader gives each thread 2048 / nthreads items: 4 or 8 waves

@@ -138,6 +138,7 @@ struct AttnPlan {
   int nwaves;      // waves per workgroup
   int chunk_keys;  // keys per split (multiple of 64)
 };
+extern int g_attn_force_splits, g_attn_force_qtw;
 AttnPlan plan_attention(int B, int K, int Hq, int Hkv, int max_total_len);
 size_t attention_workspace_floats(int B, int K, int Hq, int Hkv, int hd, const AttnPlan& p);
 hipError_t launch_attention_bf16(const bf16_t* q, const bf16_t* kcache, const bf16_t* vcache,
