@@ -130,6 +130,42 @@ def cpu_baseline(cfg, tokens_np, layers_sampled=1):
                       f"acceptance for all {B * R} rows; step = n_layers x layer + head"}
 
 
+def roofline_only(cfg, args):
+    """Isolated launches of the gate/up GEMM over `n_layers` distinct weight
+    matrices, then one 1 GiB device-to-device copy whose traffic is known
+    (1 GiB read + 1 GiB written): the calibration for byte counters."""
+    from paper_2511_22972_amd import binding as fb
+    desc = fb.make_desc(cfg)
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    es = 2 if cfg.dtype == "bf16" else 4
+    packed = []
+    for l in range(cfg.n_layers):
+        gu = torch.empty(cfg.d * 2 * cfg.ffn, dtype=tdt, device="cuda")
+        fb.fly_pack_weight(synth.make_weight(cfg, "wg", l, "cuda"), gu, 2 * cfg.ffn, 0, 2)
+        fb.fly_pack_weight(synth.make_weight(cfg, "wu", l, "cuda"), gu, 2 * cfg.ffn, 1, 2)
+        packed.append(gu)
+    xn = synth.make_hidden(cfg, cfg.M, "cuda")
+    a_buf = torch.empty(cfg.M, cfg.ffn, dtype=tdt, device="cuda")
+    counter = [0]
+
+    def gateup():
+        l = counter[0] % cfg.n_layers
+        counter[0] += 1
+        fb.fly_gateup_swiglu(xn, packed[l], a_buf)
+
+    ms = time_region(gateup, args.steps, args.warmup)
+    nbytes = cfg.d * 2 * cfg.ffn * es + cfg.M * cfg.d * es + cfg.M * cfg.ffn * es
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"kernel": "gate/up GEMM + SwiGLU", "workload": cfg.name, "launches": args.steps + args.warmup,
+                      "avg_launch_us": ms * 1e3, "bytes_per_launch": nbytes,
+                      "achieved_GBps": nbytes / (ms * 1e-3) / 1e9,
+                      "calibration": "one 1 GiB torch device copy: 1048576 KiB read, 1048576 KiB written"}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -138,6 +174,9 @@ def main():
     ap.add_argument("--workload", default="c3_70b", choices=sorted(synth.CONFIGS))
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--roofline-only", action="store_true",
+                    help="run only the dominant kernel (gate/up GEMM, isolated launches) and a 1 GiB "
+                         "device copy of known size; for hardware-counter passes (use with --layers)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)",
@@ -150,6 +189,10 @@ def main():
     cfg = synth.CONFIGS[args.workload]
     if args.layers:
         cfg = cfg.replace(n_layers=args.layers)
+
+    if args.roofline_only:
+        roofline_only(cfg, args)
+        return
 
     fb, desc, model, kv, ws = build_gpu_workload(cfg)
     row_scale = (1.0 / synth.make_row_temperature(cfg, "cuda")).reshape(-1).contiguous()
