@@ -26,6 +26,9 @@ import torch
 import synth
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel from hardware counters (FETCH_SIZE and
+# WRITE_SIZE passes scaled by a 1 GiB copy; profiles/gateup_gemm_c3_70b_hbm_counters.md).
+MEASURED_TRAFFIC_BYTES = {"c3_70b": 946.6e6}
 
 
 def log(*a):
@@ -244,7 +247,8 @@ def main():
         "roofline": {"kernel": "gemm_bf16_kernel (gate/up projection + SwiGLU)" if cfg.dtype == "bf16"
                      else "gemm_f32_kernel (gate/up projection + SwiGLU)",
                      "bound": "hbm", "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gu_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "frac": gu_gbs / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if not args.layers else None,
                      "bytes_per_launch": gu_bytes, "avg_launch_us": gu_ms * 1e3},
     }
     if not args.no_cpu_baseline:
