@@ -74,8 +74,10 @@ def check_appended_kv(wl, cfg, kv_lens, new_kv, tol):
             k_new, v_new = new_kv[b][li]                 # [R,Hkv,hd]
             got_k = kc[b, :, L:L + cfg.K + 1, :].permute(1, 0, 2)
             got_v = vc[b, :, :, L:L + cfg.K + 1].permute(2, 0, 1)
-            assert (got_k - k_new).abs().max().item() <= tol, ("k", li, b)
-            assert (got_v - v_new).abs().max().item() <= tol, ("v", li, b)
+            for name, g_t, r_t in (("k", got_k, k_new), ("v", got_v, v_new)):
+                diff = (g_t - r_t).abs()
+                # absolute tolerance for fp32 storage; one bf16 ulp where a rounding flipped
+                assert torch.all(diff <= tol + r_t.abs() * 2.0 ** -7), (name, li, b, diff.max())
 
 
 def test_layers_f32_tiny():
@@ -93,7 +95,7 @@ def test_layers_bf16(cfg, kv_lens):
     print("layer max abs err", np.abs(got - ref).max(), "max |ref|", np.abs(ref).max())
     assert np.abs(got - ref).max() < 2e-2
     # appended keys/values are bf16 values: equal up to one bf16 ulp at rounding boundaries
-    check_appended_kv(wl, cfg, kv_lens, new_kv, 2e-2)
+    check_appended_kv(wl, cfg, kv_lens, new_kv, 1e-6 if cfg.n_layers == 1 else 2e-2)
 
 
 def test_layers_bf16_single_row_tile_edges():
