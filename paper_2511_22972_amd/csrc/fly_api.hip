@@ -51,7 +51,7 @@ GemmPlan plan_gemm(int M, int N, int Kd, bool allow_split, bool need_even_nt) {
   p.mt = p.mblocks > 1 ? 9 : pick_mt(M);
   const int ntiles = N / 16;
   const int nchunks = (Kd / 32 + 3) / 4;
-  const int nt_max = p.mt <= 3 ? 4 : 2;  // accumulators plus the prefetch ring must fit the register file
+  const int nt_max = 4;
   int nt = nt_max;
   auto blocks = [&](int t) { return (ntiles + 4 * t - 1) / (4 * t); };
   if (g_force_nt) {

@@ -70,7 +70,8 @@ hipError_t launch_pack_weight(const void* src, int64_t k_in, int64_t n_src, int 
 // ---------------------------------------------------------------------------
 // bf16 weight-streaming GEMM
 // ---------------------------------------------------------------------------
-#define GEMM_KS 4  // 32-wide k-steps per LDS stage (128 k)
+// KS = 32-wide k-steps per pipeline stage: 4 (128 k) normally, 2 for the nine-row-tile variant,
+// whose accumulators leave less room for the prefetch ring.
 
 __device__ __forceinline__ float silu_f(float x) { return x / (1.f + __expf(-x)); }
 
@@ -79,48 +80,56 @@ struct GemmRegs {
   f32x4 acc[NT][MT];
 };
 
-// Issue the global loads of one k-chunk: NT x GEMM_KS weight tiles for this wave.
-// Unchecked form: every k-step of the chunk exists (branch-free, so all loads
-// of the chunk are in flight together).  Checked form (ragged last chunk):
-// k-steps at or past ks_end are replaced by zeros.
-template <int NT, bool CHECK>
-__device__ __forceinline__ void load_weight_chunk(u32x4 (&a)[NT][GEMM_KS], const u32x4* const (&wstrip)[NT],
-                                                  int ks0, int ks_end, int lane) {
+// Issue the global loads of one k-chunk: NT x KS weight tiles for this wave.
+// Always unconditional (so that all loads of a chunk are in flight together and
+// the loop around it has no branches): k-steps past the end of this workgroup's
+// range are clamped to its last k-step.  They load valid weights that are then
+// multiplied by zero activations.
+template <int NT, int KS, bool CLAMP>
+__device__ __forceinline__ void load_weight_chunk(u32x4 (&a)[NT][KS], const u32x4* const (&wstrip)[NT],
+                                                  int ks0, int ks_last, int lane) {
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
 #pragma unroll
-    for (int s = 0; s < GEMM_KS; ++s) {
-      if (!CHECK || ks0 + s < ks_end) {
-        a[j][s] = __builtin_nontemporal_load(wstrip[j] + (int64_t)(ks0 + s) * 64 + lane);
-      } else {
-        a[j][s] = u32x4{0u, 0u, 0u, 0u};
-      }
+    for (int s = 0; s < KS; ++s) {
+      const int ks = CLAMP ? min(ks0 + s, ks_last) : ks0 + s;
+      a[j][s] = __builtin_nontemporal_load(wstrip[j] + (int64_t)ks * 64 + lane);
     }
   }
 }
 
-template <int MT, int NT, int EPI>
+template <int MT, int NT, int EPI, int KS>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     const bf16_t* __restrict__ X, const u32x4* __restrict__ Wp, void* __restrict__ out,
-    const float* __restrict__ row_scale, int M, int N, int Kd, int chunks_per_split) {
+    const float* __restrict__ row_scale, int M, int N, int Kd, int chunks_per_split, int nblocks,
+    int mblocks) {
+  // Workgroup -> (column block, row block).  Workgroups are dealt to the eight
+  // XCDs (each with its own L2) round-robin by linear id.  When the activations
+  // need several row blocks, the row blocks of one column block re-read the same
+  // weight strips: they are given consecutive slots of ONE XCD so that they run
+  // together and all but the first find the strips in that XCD's L2.
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int mblock = slot % mblocks;
+  const int nblock = (slot / mblocks) * 8 + xcd;
+  if (nblock >= nblocks) return;  // padding of the last group of eight (uniform per workgroup)
   // LDS: two stages of the activation block in operand order
   // [stage][kstep][mtile][lane] x 16 bytes.
-  __shared__ u32x4 xs[2][GEMM_KS][MT][64];
+  constexpr int NFRAG_W = (KS * MT + 3) / 4;  // fragments each wave stages per chunk
+  __shared__ u32x4 xs[2][NFRAG_W * 4][64];   // fragment f = kstep * MT + row tile (padded to 4 per wave)
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // scalar: uniform branches
   const int g = lane >> 4, c16 = lane & 15;
   const int ksteps_total = Kd / 32;
-  const int nchunks_total = (ksteps_total + GEMM_KS - 1) / GEMM_KS;
+  const int nchunks_total = (ksteps_total + KS - 1) / KS;
   const int chunk_begin = blockIdx.y * chunks_per_split;
   int chunk_end = chunk_begin + chunks_per_split;
   if (chunk_end > nchunks_total) chunk_end = nchunks_total;
-  const int ks_end = min(chunk_end * GEMM_KS, ksteps_total);
-  // chunks [chunk_begin, full_end) are complete; at most one ragged chunk follows
-  const int full_end = (ks_end == chunk_end * GEMM_KS) ? chunk_end : chunk_end - 1;
-  const int mrow0 = blockIdx.z * (MT * 16);
+  const int ks_end = min(chunk_end * KS, ksteps_total);
+  const int ks_last = max(ks_end - 1, 0);
+  const int mrow0 = mblock * (MT * 16);
   const int ntiles = N / 16;
-  const int tn0 = (blockIdx.x * 4 + wave) * NT;
+  const int tn0 = (nblock * 4 + wave) * NT;
 
   // Column strips of this wave.  A strip past the last tile (ragged last
   // workgroup) is clamped to the last tile: it is loaded and multiplied like the
@@ -140,42 +149,51 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
 #pragma unroll
     for (int t = 0; t < MT; ++t) acc[j][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Activation fragments this wave stages per chunk: f = wave + 4i, i < MT
-  // (k-step f / MT, row tile f % MT).  Rows past M are clamped to row M-1: they
-  // only feed output rows that are never stored.
-  u32x4 xf[MT];
-  const bf16_t* xrow[MT];
+  // Activation fragments this wave stages per chunk: f = wave + 4i (k-step f / MT,
+  // row tile f % MT).  Fragment indices past KS*MT (padding, when KS*MT is not a
+  // multiple of 4) reload the last fragment into a padding slot nobody reads, which
+  // keeps the loop branch-free.  Rows past M are clamped to row M-1: they only
+  // feed output rows that are never stored.
+  u32x4 xf[NFRAG_W];
+  const bf16_t* xrow[NFRAG_W];
+  int xks[NFRAG_W];
 #pragma unroll
-  for (int i = 0; i < MT; ++i) {
-    int f = wave + 4 * i;
+  for (int i = 0; i < NFRAG_W; ++i) {
+    int f = min(wave + 4 * i, KS * MT - 1);
     int row = min(mrow0 + (f % MT) * 16 + c16, M - 1);
-    xrow[i] = X + (int64_t)row * Kd + (f / MT) * 32 + 8 * g;
+    xks[i] = f / MT;
+    xrow[i] = X + (int64_t)row * Kd + xks[i] * 32 + 8 * g;
   }
-  auto load_x = [&](int chunk, bool check) {
+  // k-steps at or past ks_end (ragged last chunk, or the up to two surplus
+  // pipeline steps) read a clamped, valid address; they are replaced by zeros
+  // when written to LDS (not at load time, which would wait for the load).
+  auto load_x = [&](int chunk) {
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      int kstep = chunk * GEMM_KS + (wave + 4 * i) / MT;
-      if (!check || kstep < ks_end) {
-        xf[i] = *(const u32x4*)(xrow[i] + (int64_t)chunk * (GEMM_KS * 32));
-      } else {
-        xf[i] = u32x4{0u, 0u, 0u, 0u};
-      }
+    for (int i = 0; i < NFRAG_W; ++i) {
+      const int kc = min(chunk * KS + xks[i], ks_last) - xks[i];  // xrow already points at k-step xks[i]
+      xf[i] = *(const u32x4*)(xrow[i] + (int64_t)kc * 32);
     }
   };
-  auto store_x = [&](int stage) {
+  // the same for a chunk known to lie wholly inside the range
+  auto load_x_inner = [&](int chunk) {
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
-      int f = wave + 4 * i;
-      xs[stage][f / MT][f % MT][lane] = xf[i];
+    for (int i = 0; i < NFRAG_W; ++i) xf[i] = *(const u32x4*)(xrow[i] + (int64_t)chunk * (KS * 32));
+  };
+  auto store_x = [&](int stage, int chunk) {  // chunk < 0: no masking needed
+#pragma unroll
+    for (int i = 0; i < NFRAG_W; ++i) {
+      u32x4 v = xf[i];
+      if (chunk >= 0 && chunk * KS + xks[i] >= ks_end) v = u32x4{0u, 0u, 0u, 0u};
+      xs[stage][wave + 4 * i][lane] = v;
     }
   };
 
-  auto compute = [&](const u32x4 (&a)[NT][GEMM_KS], int stage) {
+  auto compute = [&](const u32x4 (&a)[NT][KS], int stage) {
 #pragma unroll
-    for (int s = 0; s < GEMM_KS; ++s) {
+    for (int s = 0; s < KS; ++s) {
 #pragma unroll
       for (int t = 0; t < MT; ++t) {
-        u32x4 braw = xs[stage][s][t][lane];
+        u32x4 braw = xs[stage][s * MT + t][lane];
         bf16x8 b = __builtin_bit_cast(bf16x8, braw);
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
@@ -191,59 +209,46 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
   // The activation loads of chunk c+1 are issued BEFORE the weight loads of
   // chunk c+2, so that writing them to LDS at the end of the step waits only
   // for them (loads retire in order) and leaves the weight loads in flight.
-  u32x4 a0[NT][GEMM_KS], a1[NT][GEMM_KS], a2[NT][GEMM_KS];
+  // The loop body has no conditionals at all -- with branches in it the
+  // compiler waits for every outstanding load before each multiply and keeps a
+  // second copy of the accumulators.  The trip count is rounded up to a
+  // multiple of three steps; surplus steps multiply by zero activations.
+  u32x4 a0[NT][KS], a1[NT][KS], a2[NT][KS];
   int stage = 0;
 
-#define FLY_GEMM_STEP(CUR, NXT2, c)                                                     \
-  {                                                                                     \
-    const int c_ = (c);                                                                 \
-    if (c_ + 1 < chunk_end) load_x(c_ + 1, c_ + 1 >= full_end);                          \
-    if (c_ + 2 < full_end) load_weight_chunk<NT, false>(NXT2, wstrip, (c_ + 2) * GEMM_KS, ks_end, lane); \
-    else if (c_ + 2 < chunk_end) load_weight_chunk<NT, true>(NXT2, wstrip, (c_ + 2) * GEMM_KS, ks_end, lane); \
-    compute(CUR, stage);                                                                \
-    if (c_ + 1 < chunk_end) store_x(stage ^ 1);                                         \
-    __syncthreads();                                                                    \
-    stage ^= 1;                                                                         \
-  }
-
-#define FLY_GEMM_STEP_FAST(CUR, NXT2, c)                                                \
-  {                                                                                     \
-    load_x((c) + 1, false);                                                             \
-    load_weight_chunk<NT, false>(NXT2, wstrip, ((c) + 2) * GEMM_KS, ks_end, lane);      \
-    compute(CUR, stage);                                                                \
-    store_x(stage ^ 1);                                                                 \
-    __syncthreads();                                                                    \
-    stage ^= 1;                                                                         \
+#define FLY_GEMM_STEP(CUR, NXT2, c, LOADX, CLAMP)                      \
+  {                                                                    \
+    LOADX((c) + 1);                                                    \
+    load_weight_chunk<NT, KS, CLAMP>(NXT2, wstrip, ((c) + 2) * KS, ks_last, lane); \
+    compute(CUR, stage);                                               \
+    store_x(stage ^ 1, CLAMP ? (c) + 1 : -1);                          \
+    __syncthreads();                                                   \
+    stage ^= 1;                                                        \
   }
 
   if (chunk_begin < chunk_end) {
-    load_x(chunk_begin, chunk_begin >= full_end);
-    if (chunk_begin < full_end) load_weight_chunk<NT, false>(a0, wstrip, chunk_begin * GEMM_KS, ks_end, lane);
-    else load_weight_chunk<NT, true>(a0, wstrip, chunk_begin * GEMM_KS, ks_end, lane);
-    if (chunk_begin + 1 < full_end) load_weight_chunk<NT, false>(a1, wstrip, (chunk_begin + 1) * GEMM_KS, ks_end, lane);
-    else if (chunk_begin + 1 < chunk_end) load_weight_chunk<NT, true>(a1, wstrip, (chunk_begin + 1) * GEMM_KS, ks_end, lane);
-    store_x(0);
+    load_x(chunk_begin);
+    load_weight_chunk<NT, KS, true>(a0, wstrip, chunk_begin * KS, ks_last, lane);
+    load_weight_chunk<NT, KS, true>(a1, wstrip, (chunk_begin + 1) * KS, ks_last, lane);
+    store_x(0, chunk_begin);
     __syncthreads();
     int c = chunk_begin;
-    // Steady state: three branch-free steps per trip (the ring returns to a0),
-    // taken while every chunk touched is complete.  Without conditionals in the
-    // body the wait counts before each multiply cover only the buffer in use.
-    while (c + 4 < full_end) {
-      FLY_GEMM_STEP_FAST(a0, a2, c);
-      FLY_GEMM_STEP_FAST(a1, a0, c + 1);
-      FLY_GEMM_STEP_FAST(a2, a1, c + 2);
+    // steady state: every chunk touched (up to c + 4) lies wholly inside the range,
+    // so addresses are plain base + offset
+    const int inner_end = ks_end / KS;  // chunks below this index are complete
+    while (c + 4 < inner_end) {
+      FLY_GEMM_STEP(a0, a2, c, load_x_inner, false);
+      FLY_GEMM_STEP(a1, a0, c + 1, load_x_inner, false);
+      FLY_GEMM_STEP(a2, a1, c + 2, load_x_inner, false);
       c += 3;
     }
-    // Tail: the last few chunks, with bounds checks (a0 holds chunk c, a1 chunk c+1).
+    // last few chunks: clamped addresses, zero activations past the end
     for (; c < chunk_end; c += 3) {
-      FLY_GEMM_STEP(a0, a2, c);
-      if (c + 1 >= chunk_end) break;
-      FLY_GEMM_STEP(a1, a0, c + 1);
-      if (c + 2 >= chunk_end) break;
-      FLY_GEMM_STEP(a2, a1, c + 2);
+      FLY_GEMM_STEP(a0, a2, c, load_x, true);
+      if (c + 1 < chunk_end) FLY_GEMM_STEP(a1, a0, c + 1, load_x, true);
+      if (c + 2 < chunk_end) FLY_GEMM_STEP(a2, a1, c + 2, load_x, true);
     }
   }
-#undef FLY_GEMM_STEP_FAST
 #undef FLY_GEMM_STEP
 
   // ---- epilogues.  Lane holds out^T[n = 16*tile + 4g + r][m = 16t + c16], r = 0..3.
@@ -279,8 +284,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     }
   } else {  // EPI_LMHEAD: per-wave softmax statistics of this wave's columns
     f32x4* o = (f32x4*)out;
-    const int nparts = gridDim.x * 4;
-    const int part = blockIdx.x * 4 + wave;
+    const int nparts = nblocks * 4;
+    const int part = nblock * 4 + wave;
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
       int m = mrow0 + t * 16 + c16;
@@ -333,25 +338,26 @@ template <int MT, int NT>
 static hipError_t launch_gemm_mt_nt(const bf16_t* X, const bf16_t* Wp, void* out,
                                     const float* row_scale, int M, int N, int Kd,
                                     const GemmPlan& plan, int epi, hipStream_t st) {
+  constexpr int KS = MT >= 9 ? 2 : 4;
   int ntiles = N / 16;
   int nblocks = (ntiles + 4 * NT - 1) / (4 * NT);
-  int nchunks = (Kd / 32 + GEMM_KS - 1) / GEMM_KS;
+  int nchunks = (Kd / 32 + KS - 1) / KS;
   int cps = (nchunks + plan.splits - 1) / plan.splits;
-  dim3 grid(nblocks, plan.splits, plan.mblocks), block(256);
+  dim3 grid((nblocks + 7) / 8 * 8 * plan.mblocks, plan.splits, 1), block(256);
   const u32x4* W4 = (const u32x4*)Wp;
   if (epi == EPI_PARTIAL) {
-    hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_PARTIAL>), grid, block, 0, st, X, W4, out,
-                       row_scale, M, N, Kd, cps);
+    hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_PARTIAL, KS>), grid, block, 0, st, X, W4, out,
+                       row_scale, M, N, Kd, cps, nblocks, plan.mblocks);
   } else if (epi == EPI_SWIGLU) {
     if constexpr (NT >= 2) {
-      hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_SWIGLU>), grid, block, 0, st, X, W4, out,
-                         row_scale, M, N, Kd, cps);
+      hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_SWIGLU, KS>), grid, block, 0, st, X, W4, out,
+                         row_scale, M, N, Kd, cps, nblocks, plan.mblocks);
     } else {
       return hipErrorInvalidValue;
     }
   } else {
-    hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_LMHEAD>), grid, block, 0, st, X, W4, out,
-                       row_scale, M, N, Kd, cps);
+    hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_LMHEAD, KS>), grid, block, 0, st, X, W4, out,
+                       row_scale, M, N, Kd, cps, nblocks, plan.mblocks);
   }
   return hipGetLastError();
 }
@@ -363,10 +369,7 @@ static hipError_t launch_gemm_mt(const bf16_t* X, const bf16_t* Wp, void* out,
   switch (plan.nt) {
     case 1: return launch_gemm_mt_nt<MT, 1>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
     case 2: return launch_gemm_mt_nt<MT, 2>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 4:
-      // five or nine row tiles times four column tiles plus the prefetch ring do not fit the register file
-      if constexpr (MT <= 3) return launch_gemm_mt_nt<MT, 4>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-      else return hipErrorInvalidValue;
+    case 4: return launch_gemm_mt_nt<MT, 4>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
   }
   return hipErrorInvalidValue;
 }
