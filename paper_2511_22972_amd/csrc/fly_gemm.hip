@@ -188,13 +188,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     }
   };
 
+  // All activation fragments of the chunk are requested from LDS up front, so
+  // that the reads are in flight together and only the first multiply waits
+  // for LDS latency (issued pairwise just before use, each pair stalls the
+  // matrix pipe for a full LDS round trip).
   auto compute = [&](const u32x4 (&a)[NT][KS], int stage) {
+    u32x4 bfrag[KS][MT];
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+      for (int t = 0; t < MT; ++t) bfrag[s][t] = xs[stage][s * MT + t][lane];
+    __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of the multiplies
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
 #pragma unroll
       for (int t = 0; t < MT; ++t) {
-        u32x4 braw = xs[stage][s * MT + t][lane];
-        bf16x8 b = __builtin_bit_cast(bf16x8, braw);
+        bf16x8 b = __builtin_bit_cast(bf16x8, bfrag[s][t]);
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
           bf16x8 av = __builtin_bit_cast(bf16x8, a[j][s]);
@@ -202,6 +211,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
         }
       }
     }
+    // ... and the LDS write of the next chunk's activations (which waits for their
+    // global loads) behind the multiplies
+    __builtin_amdgcn_sched_barrier(0);
   };
 
   // Software pipeline over k-chunks with a ring of three weight buffers: while
