@@ -126,6 +126,7 @@ const char* fly_strerror(fly_status s);
  * Launch-shape knobs for experiments (process-wide, not thread-safe):
  *   "gemm_nt"      16-column weight tiles per wavefront: 1, 2, 4; 0 = automatic
  *   "gemm_splits"  split-K factor of the projections: 1..16; 0 = automatic
+ *   "gemm_mt_max"  most 16-row activation tiles one workgroup holds: 5 or 9 (default 9)
  *   "attn_splits"  cache splits per (sequence, KV head): 1..256; 0 = automatic
  *   "attn_qtw"     16-row query tiles per wavefront: 1..3; 0 = automatic
  *   "target_wgs"   workgroups a launch aims for (default 256, one per compute unit)

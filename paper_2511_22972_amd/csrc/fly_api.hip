@@ -12,6 +12,7 @@ namespace {
 int g_force_nt = 0;
 int g_force_splits = 0;
 int g_target_wgs = 256;
+int g_mt_max = 9;
 
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 
@@ -47,8 +48,9 @@ int splits_for(int nblocks, int nchunks) {
 
 GemmPlan plan_gemm(int M, int N, int Kd, bool allow_split, bool need_even_nt) {
   GemmPlan p;
-  p.mblocks = (M + 143) / 144;
-  p.mt = p.mblocks > 1 ? 9 : pick_mt(M);
+  const int rows_max = g_mt_max * 16;
+  p.mblocks = (M + rows_max - 1) / rows_max;
+  p.mt = p.mblocks > 1 ? g_mt_max : pick_mt(M);
   const int ntiles = N / 16;
   const int nchunks = (Kd / 32 + 3) / 4;
   const int nt_max = 4;
@@ -312,6 +314,9 @@ fly_status fly_set_tuning(const char* key, int32_t value) {
   } else if (!strcmp(key, "attn_qtw")) {
     if (value < 0 || value > 3) return FLY_ERR_BAD_SHAPE;
     g_attn_force_qtw = value;
+  } else if (!strcmp(key, "gemm_mt_max")) {
+    if (value != 5 && value != 9) return FLY_ERR_BAD_SHAPE;
+    g_mt_max = value;
   } else if (!strcmp(key, "target_wgs")) {
     if (value < 1) return FLY_ERR_BAD_SHAPE;
     g_target_wgs = value;

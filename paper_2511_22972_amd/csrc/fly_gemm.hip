@@ -98,7 +98,7 @@ __device__ __forceinline__ void load_weight_chunk(u32x4 (&a)[NT][KS], const u32x
   }
 }
 
-template <int MT, int NT, int EPI, int KS>
+template <int MT, int NT, int EPI, int KS, int RING>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     const bf16_t* __restrict__ X, const u32x4* __restrict__ Wp, void* __restrict__ out,
     const float* __restrict__ row_scale, int M, int N, int Kd, int chunks_per_split, int nblocks,
@@ -216,52 +216,57 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     __builtin_amdgcn_sched_barrier(0);
   };
 
-  // Software pipeline over k-chunks with a ring of three weight buffers: while
-  // chunk c is multiplied, the weights of chunks c+1 and c+2 are in flight.
-  // The activation loads of chunk c+1 are issued BEFORE the weight loads of
-  // chunk c+2, so that writing them to LDS at the end of the step waits only
-  // for them (loads retire in order) and leaves the weight loads in flight.
-  // The loop body has no conditionals at all -- with branches in it the
-  // compiler waits for every outstanding load before each multiply and keeps a
-  // second copy of the accumulators.  The trip count is rounded up to a
-  // multiple of three steps; surplus steps multiply by zero activations.
-  u32x4 a0[NT][KS], a1[NT][KS], a2[NT][KS];
+  // Software pipeline over k-chunks with a ring of RING weight buffers in
+  // registers: while chunk c is multiplied, the weights of chunks c+1 ..
+  // c+RING-1 are in flight (the bytes in flight per compute unit are what
+  // decides the achieved HBM bandwidth).  The activation loads of chunk c+1 are
+  // issued BEFORE the weight loads of chunk c+RING-1, so that writing them to
+  // LDS at the end of the step waits only for them (loads retire in order) and
+  // leaves the weight loads in flight.  Step bodies have no conditionals -- with
+  // branches in them the compiler waits for every outstanding load before each
+  // multiply and keeps a second copy of the accumulators; the tail guards whole
+  // steps instead.
+  u32x4 ring[RING][NT][KS];
   int stage = 0;
-
-#define FLY_GEMM_STEP(CUR, NXT2, c, LOADX, CLAMP)                      \
-  {                                                                    \
-    LOADX((c) + 1);                                                    \
-    load_weight_chunk<NT, KS, CLAMP>(NXT2, wstrip, ((c) + 2) * KS, ks_last, lane); \
-    compute(CUR, stage);                                               \
-    store_x(stage ^ 1, CLAMP ? (c) + 1 : -1);                          \
-    __syncthreads();                                                   \
-    stage ^= 1;                                                        \
-  }
 
   if (chunk_begin < chunk_end) {
     load_x(chunk_begin);
-    load_weight_chunk<NT, KS, true>(a0, wstrip, chunk_begin * KS, ks_last, lane);
-    load_weight_chunk<NT, KS, true>(a1, wstrip, (chunk_begin + 1) * KS, ks_last, lane);
+#pragma unroll
+    for (int r = 0; r < RING - 1; ++r)
+      load_weight_chunk<NT, KS, true>(ring[r], wstrip, (chunk_begin + r) * KS, ks_last, lane);
     store_x(0, chunk_begin);
     __syncthreads();
     int c = chunk_begin;
-    // steady state: every chunk touched (up to c + 4) lies wholly inside the range,
-    // so addresses are plain base + offset
+    // steady state: every chunk touched (up to c + 2 RING - 2) lies wholly inside
+    // the range, so addresses are plain base + offset
     const int inner_end = ks_end / KS;  // chunks below this index are complete
-    while (c + 4 < inner_end) {
-      FLY_GEMM_STEP(a0, a2, c, load_x_inner, false);
-      FLY_GEMM_STEP(a1, a0, c + 1, load_x_inner, false);
-      FLY_GEMM_STEP(a2, a1, c + 2, load_x_inner, false);
-      c += 3;
+    while (c + 2 * RING - 2 < inner_end) {
+#pragma unroll
+      for (int r = 0; r < RING; ++r) {
+        load_x_inner(c + r + 1);
+        load_weight_chunk<NT, KS, false>(ring[(r + RING - 1) % RING], wstrip, (c + r + RING - 1) * KS, ks_last, lane);
+        compute(ring[r], stage);
+        store_x(stage ^ 1, -1);
+        __syncthreads();
+        stage ^= 1;
+      }
+      c += RING;
     }
     // last few chunks: clamped addresses, zero activations past the end
-    for (; c < chunk_end; c += 3) {
-      FLY_GEMM_STEP(a0, a2, c, load_x, true);
-      if (c + 1 < chunk_end) FLY_GEMM_STEP(a1, a0, c + 1, load_x, true);
-      if (c + 2 < chunk_end) FLY_GEMM_STEP(a2, a1, c + 2, load_x, true);
+    for (; c < chunk_end; c += RING) {
+#pragma unroll
+      for (int r = 0; r < RING; ++r) {
+        if (r == 0 || c + r < chunk_end) {
+          load_x(c + r + 1);
+          load_weight_chunk<NT, KS, true>(ring[(r + RING - 1) % RING], wstrip, (c + r + RING - 1) * KS, ks_last, lane);
+          compute(ring[r], stage);
+          store_x(stage ^ 1, c + r + 1);
+          __syncthreads();
+          stage ^= 1;
+        }
+      }
     }
   }
-#undef FLY_GEMM_STEP
 
   // ---- epilogues.  Lane holds out^T[n = 16*tile + 4g + r][m = 16t + c16], r = 0..3.
   if constexpr (EPI == EPI_PARTIAL) {
@@ -351,6 +356,7 @@ static hipError_t launch_gemm_mt_nt(const bf16_t* X, const bf16_t* Wp, void* out
                                     const float* row_scale, int M, int N, int Kd,
                                     const GemmPlan& plan, int epi, hipStream_t st) {
   constexpr int KS = MT >= 9 ? 2 : 4;
+  constexpr int RING = MT >= 9 ? 4 : 3;  // the same bytes in flight with half-size chunks
   int ntiles = N / 16;
   int nblocks = (ntiles + 4 * NT - 1) / (4 * NT);
   int nchunks = (Kd / 32 + KS - 1) / KS;
@@ -358,17 +364,17 @@ static hipError_t launch_gemm_mt_nt(const bf16_t* X, const bf16_t* Wp, void* out
   dim3 grid((nblocks + 7) / 8 * 8 * plan.mblocks, plan.splits, 1), block(256);
   const u32x4* W4 = (const u32x4*)Wp;
   if (epi == EPI_PARTIAL) {
-    hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_PARTIAL, KS>), grid, block, 0, st, X, W4, out,
+    hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_PARTIAL, KS, RING>), grid, block, 0, st, X, W4, out,
                        row_scale, M, N, Kd, cps, nblocks, plan.mblocks);
   } else if (epi == EPI_SWIGLU) {
     if constexpr (NT >= 2) {
-      hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_SWIGLU, KS>), grid, block, 0, st, X, W4, out,
+      hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_SWIGLU, KS, RING>), grid, block, 0, st, X, W4, out,
                          row_scale, M, N, Kd, cps, nblocks, plan.mblocks);
     } else {
       return hipErrorInvalidValue;
     }
   } else {
-    hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_LMHEAD, KS>), grid, block, 0, st, X, W4, out,
+    hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_LMHEAD, KS, RING>), grid, block, 0, st, X, W4, out,
                        row_scale, M, N, Kd, cps, nblocks, plan.mblocks);
   }
   return hipGetLastError();
