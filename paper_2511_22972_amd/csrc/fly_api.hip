@@ -13,6 +13,7 @@ int g_force_nt = 0;
 int g_force_splits = 0;
 int g_target_wgs = 256;
 int g_mt_max = 9;
+int g_tiled = 0;  // 0 automatic, 1 never, 2, 3 or 6: always, with that workgroup shape
 
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 
@@ -46,8 +47,43 @@ int splits_for(int nblocks, int nchunks) {
   return (nchunks + cps - 1) / cps;
 }
 
+// Above 144 rows the weight-streaming kernel would re-read the weights once per
+// row block; the LDS-tiled kernel takes over.  Its workgroups cover 128, 192 or
+// 384 rows: the shape that pads M least wins, the larger one on a tie (fewer
+// bytes staged per flop).
+GemmPlan plan_gemm_tiled(int M, int N, int Kd, bool allow_split, int forced) {
+  GemmPlan p{1, 1, 1, 1, 3};
+  auto padded = [&](int shape) {
+    const int rows = gemm_bf16_tiled_rows(shape);
+    return (M + rows - 1) / rows * rows;
+  };
+  if (forced) {
+    p.tiled = forced;
+  } else {
+    p.tiled = 2;
+    if (padded(3) <= padded(p.tiled)) p.tiled = 3;
+    if (padded(6) <= padded(p.tiled)) p.tiled = 6;
+  }
+  p.mblocks = padded(p.tiled) / gemm_bf16_tiled_rows(p.tiled);
+  if (allow_split) {
+    const int cols = gemm_bf16_tiled_cols(p.tiled);
+    const int wgs = (N + cols - 1) / cols * p.mblocks;
+    const int ktiles = Kd / 32;
+    int s = g_force_splits ? g_force_splits : (g_target_wgs + wgs / 2) / wgs;
+    int max_splits = ktiles / 16;  // at least sixteen k-steps per split
+    if (s > max_splits) s = max_splits;
+    if (s > 16) s = 16;
+    if (s < 1) s = 1;
+    int kps = (ktiles + s - 1) / s;
+    p.splits = (ktiles + kps - 1) / kps;
+  }
+  return p;
+}
+
 GemmPlan plan_gemm(int M, int N, int Kd, bool allow_split, bool need_even_nt) {
+  if (g_tiled >= 2 || (g_tiled == 0 && M > 144)) return plan_gemm_tiled(M, N, Kd, allow_split, g_tiled);
   GemmPlan p;
+  p.tiled = 0;
   const int rows_max = g_mt_max * 16;
   p.mblocks = (M + rows_max - 1) / rows_max;
   p.mt = p.mblocks > 1 ? g_mt_max : pick_mt(M);
@@ -298,7 +334,7 @@ const char* fly_strerror(fly_status s) {
   return "unknown status";
 }
 
-// Tuning knobs for experiments: "gemm_nt" (1, 2, 4; 0 = automatic),
+// Tuning knobs for experiments: "gemm_nt" (1, 2, 4; 0 = automatic), "gemm_tiled",
 // "gemm_splits" (0 = automatic), "target_wgs" (workgroups a launch aims for).
 fly_status fly_set_tuning(const char* key, int32_t value) {
   if (!key) return FLY_ERR_NULL_POINTER;
@@ -317,6 +353,9 @@ fly_status fly_set_tuning(const char* key, int32_t value) {
   } else if (!strcmp(key, "gemm_mt_max")) {
     if (value != 5 && value != 9) return FLY_ERR_BAD_SHAPE;
     g_mt_max = value;
+  } else if (!strcmp(key, "gemm_tiled")) {
+    if (value != 0 && value != 1 && gemm_bf16_tiled_rows(value) == 0) return FLY_ERR_BAD_SHAPE;
+    g_tiled = value;
   } else if (!strcmp(key, "target_wgs")) {
     if (value < 1) return FLY_ERR_BAD_SHAPE;
     g_target_wgs = value;

@@ -90,6 +90,8 @@ struct GemmPlan {
   int nt;      // 16-column weight tiles per wave (1,2,4)
   int splits;  // split-K factor (partial results go to the workspace)
   int mblocks; // row blocks (activations beyond 144 rows re-stream the weights)
+  int tiled;   // 0: weight-streaming kernel (mt, nt as above); else the LDS-tiled kernel with
+               // workgroups of 256 columns x 128 (2), 192 (3) or 384 (6) rows (mt, nt unused)
 };
 
 enum GemmEpilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_LMHEAD = 2 };
@@ -106,6 +108,12 @@ hipError_t launch_pack_weight(const void* src, int64_t k_in, int64_t n_src, int 
 hipError_t launch_gemm_bf16(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale,
                             int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st);
 int gemm_bf16_lmhead_parts(int N, const GemmPlan& plan);
+// LDS-tiled variant for large M (called through launch_gemm_bf16 when plan.tiled != 0).
+hipError_t launch_gemm_bf16_tiled(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale,
+                                  int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st);
+int gemm_bf16_tiled_lmhead_parts(int N, int tiled);
+int gemm_bf16_tiled_rows(int tiled);
+int gemm_bf16_tiled_cols(int tiled);
 
 // fp32 GEMM (weights row-major [Kd,N]) with the same epilogues; no split-K.
 hipError_t launch_gemm_f32(const float* X, const float* W, void* out, const float* row_scale, int M,

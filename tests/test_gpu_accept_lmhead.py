@@ -122,6 +122,23 @@ def test_lmhead_bf16(fb, M, d, V):
     check_lmhead(got, ref, 2e-3)
 
 
+@pytest.mark.parametrize("M,d,V", [(200, 256, 2048 + 48), (300, 544, 16 * 131), (1088, 512, 4096),
+                                   (145, 32, 16), (385, 96, 272)])
+def test_lmhead_bf16_many_rows(fb, M, d, V):
+    """Row counts that take the LDS-tiled GEMM (workgroups of 128 or 192 rows): ragged last row
+    block, a vocabulary that is not a multiple of the 256-column block, fewer k-steps than the
+    prefetch ring is deep."""
+    got, ref = lmhead_case(fb, M, d, V, "bf16", hidden_std=4.0)
+    check_lmhead(got, ref, 2e-3)
+    for wm in (2, 3, 6):
+        fb.fly_set_tuning("gemm_tiled", wm)
+        try:
+            got, ref = lmhead_case(fb, M, d, V, "bf16", hidden_std=4.0, seed=3)
+        finally:
+            fb.fly_set_tuning("gemm_tiled", 0)
+        check_lmhead(got, ref, 2e-3)
+
+
 def test_lmhead_planted_argmax_and_ties(fb):
     V, d, M = 8192, 64, 8
     cols = [0, 15, 16, 255, 256, 4095, 8190, 8191]

@@ -239,3 +239,57 @@ def test_gateup_swiglu_stage_bf16():
         diff = (a.float().cpu().double() - ref).abs()
         assert torch.all(diff <= ref.abs() * 2.0 ** -7 + 1e-7), (M, d, F, diff.max())
         assert (diff == 0).double().mean().item() > 0.99
+
+
+@pytest.mark.gpu
+def test_gateup_swiglu_stage_bf16_many_rows():
+    """The same stage above 144 rows, where the LDS-tiled GEMM takes over."""
+    from paper_2511_22972_amd import binding as fb
+    cases = [(M, d, F, 0) for M, d, F in ((200, 128, 16 * 37), (389, 256, 1056), (145, 32, 16), (1088, 64, 512))]
+    cases += [(389, 256, 1056, shape) for shape in (2, 3, 6)]
+    for M, d, F, shape in cases:
+        fb.fly_set_tuning("gemm_tiled", shape)
+        x = synth.hash_normal(6, 320, (M, d), 1.0, torch.bfloat16, "cuda")
+        wg = synth.hash_normal(6, 321, (d, F), 0.05, torch.bfloat16, "cuda")
+        wu = synth.hash_normal(6, 322, (d, F), 0.05, torch.bfloat16, "cuda")
+        wp = torch.empty(d * 2 * F, dtype=torch.bfloat16, device="cuda")
+        fb.fly_pack_weight(wg, wp, 2 * F, 0, 2)
+        fb.fly_pack_weight(wu, wp, 2 * F, 1, 2)
+        a = torch.zeros(M, F, dtype=torch.bfloat16, device="cuda")
+        try:
+            fb.fly_gateup_swiglu(x, wp, a)
+        finally:
+            fb.fly_set_tuning("gemm_tiled", 0)
+        torch.cuda.synchronize()
+        xd = x.float().cpu().double()
+        ref = O.round_to_bf16(O.silu(xd @ wg.float().cpu().double()) * (xd @ wu.float().cpu().double()))
+        diff = (a.float().cpu().double() - ref).abs()
+        assert torch.all(diff <= ref.abs() * 2.0 ** -7 + 1e-7), (M, d, F, shape, diff.max())
+        assert (diff == 0).double().mean().item() > 0.99
+
+
+@pytest.mark.gpu
+def test_projection_partials_bf16():
+    """Split-K projection GEMM alone, both kernels: the partial sums add up to x W."""
+    from paper_2511_22972_amd import binding as fb
+    cases = [(M, Kd, N, 0) for M, Kd, N in ((36, 1024, 272), (100, 4096, 512), (200, 2048, 528),
+                                            (389, 512, 1040), (1088, 1024, 256), (145, 32, 16))]
+    cases += [(389, 2048, 528, shape) for shape in (2, 3, 6)]
+    for M, Kd, N, shape in cases:
+        fb.fly_set_tuning("gemm_tiled", shape)
+        x = synth.hash_normal(7, 330, (M, Kd), 1.0, torch.bfloat16, "cuda")
+        w = synth.hash_normal(7, 331, (Kd, N), 0.05, torch.bfloat16, "cuda")
+        wp = torch.empty(Kd * N, dtype=torch.bfloat16, device="cuda")
+        fb.fly_pack_weight(w, wp, N)
+        partial = torch.full((16 * M * N,), float("nan"), dtype=torch.float32, device="cuda")
+        try:
+            splits = fb.fly_proj_partial(x, wp, partial, N)
+        finally:
+            fb.fly_set_tuning("gemm_tiled", 0)
+        torch.cuda.synchronize()
+        assert 1 <= splits <= 16
+        got = partial[: splits * M * N].view(splits, M, N).double().sum(0).cpu()
+        ref = x.float().cpu().double() @ w.float().cpu().double()
+        scale = ref.abs().max().item()
+        assert torch.isfinite(got).all()
+        assert (got - ref).abs().max().item() <= 2e-5 * scale + 1e-6, (M, Kd, N, shape, splits)
