@@ -130,7 +130,7 @@ const char* fly_strerror(fly_status s);
  *   "gemm_tiled"   0 = the LDS-tiled GEMM above 144 rows (automatic), 1 = never,
  *                  2, 3 or 6 = always, with workgroups of 128, 192 or 384 rows
  *   "attn_splits"  cache splits per (sequence, KV head): 1..256; 0 = automatic
- *   "attn_qtw"     16-row query tiles per wavefront: 1..3; 0 = automatic
+ *   "attn_block_tiles"  most 32-row query tiles per workgroup: 1..8; 0 = automatic (8)
  *   "target_wgs"   workgroups a launch aims for (default 256, one per compute unit)
  * Workspace sizes depend on them: query again after a change.
  */

@@ -170,11 +170,11 @@ fly_status make_plans(const fly_model_desc* desc, int B, int K, int max_kv_len, 
     pl->down = plan_gemm(M, desc->d, desc->ffn, true, false);
     pl->lm = plan_gemm(M, desc->vocab, desc->d, false, false);
     pl->attn = plan_attention(B, K, desc->n_q_heads, desc->n_kv_heads, max_kv_len + K + 1);
-    if (pl->attn.nwaves > 8) return FLY_ERR_BAD_SHAPE;  // more than 384 query rows per KV head
+    if (pl->attn.qblocks > 16) return FLY_ERR_BAD_SHAPE;  // more than 4096 query rows per KV head
   } else {
     GemmPlan one{1, 1, 1, 1};
     pl->qkv = pl->wo = pl->gateup = pl->down = pl->lm = one;
-    pl->attn = AttnPlan{1, 1, 1, 64};
+    pl->attn = AttnPlan{1, 64, 1, 1};
   }
   pl->lm_parts = desc->dtype == FLY_BF16 ? gemm_bf16_lmhead_parts(desc->vocab, pl->lm)
                                          : gemm_f32_lmhead_parts(desc->vocab);
@@ -347,9 +347,9 @@ fly_status fly_set_tuning(const char* key, int32_t value) {
   } else if (!strcmp(key, "attn_splits")) {
     if (value < 0 || value > 256) return FLY_ERR_BAD_SHAPE;
     g_attn_force_splits = value;
-  } else if (!strcmp(key, "attn_qtw")) {
-    if (value < 0 || value > 3) return FLY_ERR_BAD_SHAPE;
-    g_attn_force_qtw = value;
+  } else if (!strcmp(key, "attn_block_tiles")) {
+    if (value < 0 || value > 8) return FLY_ERR_BAD_SHAPE;
+    g_attn_force_block_tiles = value;
   } else if (!strcmp(key, "gemm_mt_max")) {
     if (value != 5 && value != 9) return FLY_ERR_BAD_SHAPE;
     g_mt_max = value;

@@ -9,6 +9,14 @@
 // unnormalised output, a running maximum and a sum per query row, and a
 // second kernel merges the splits.
 //
+// A workgroup of eight waves streams 64-key stages through an LDS ring filled
+// by LDS-direct loads.  With up to four 32-row query tiles (KS = 2) wave w owns
+// tile w/2 and the keys 32 (w%2) .. +31 of every stage, so that few rows still
+// spread over all four SIMDs; the two key halves of a tile are merged through
+// LDS at the end.  With five to eight tiles (KS = 1) wave w owns tile w and all
+// 64 keys of a stage.  More than 256 rows are divided over several query blocks
+// (workgroups) that stream the same keys.
+//
 // Layouts: keys [B, Hkv, capacity, hd]; values transposed [B, Hkv, hd, capacity];
 // q and o [M, Hq*hd].  Query row r of a KV head is (position i = r / G,
 // head kvh*G + r % G).
@@ -19,30 +27,73 @@
 #define ATT_KC 64                      // keys per LDS stage
 #define ATT_KROW (ATT_HD * 2)           // bytes per key row in LDS
 #define ATT_VROW (ATT_KC * 2)           // bytes per V^T row in LDS
-#define ATT_STAGE_BYTES (ATT_KC * ATT_KROW + ATT_HD * ATT_VROW)  // 32 KiB; two stages = 64 KiB
+#define ATT_STAGE_BYTES (ATT_KC * ATT_KROW + ATT_HD * ATT_VROW)  // 32 KiB
+#define ATT_NWAVES 8
+#define ATT_NSTG 4                      // stages in the LDS ring (128 KiB); three are in flight
 // Rows are stored unpadded; the 16-byte pieces of a row are permuted so that
-// both the row-wise stores and the operand-order loads spread over all banks:
-// key rows XOR the piece index with (key & 15), V^T rows with ((row >> 1) & 7).
-#define ATT_KSWZ(key, piece) (((piece) ^ ((key) & 15)) * 16)
-#define ATT_VSWZ(row, piece) (((piece) ^ (((row) >> 1) & 7)) * 16)
+// the operand-order loads of eight consecutive lanes spread over all banks.
+// Key rows XOR the piece index with the low four bits of the key, bit 2
+// flipped when bit 3 is set (a lane octet reads keys k..k+3 and k+8..k+11, see
+// ATT_KPERM); V^T rows XOR it with (row & 7).
+#define ATT_KSWZ(key, piece) (((piece) ^ (((key) & 15) ^ ((((key) >> 3) & 1) << 2))) * 16)
+#define ATT_VSWZ(row, piece) (((piece) ^ ((row) & 7)) * 16)
+// Row i of a 32-key score tile holds key ATT_KPERM(i) of the tile (bits 2 and 3
+// of i swapped).  With this order the sixteen scores a lane holds of one query
+// row are two runs of eight consecutive keys, i.e. exactly the operand order
+// of the P V product, whose V^T fragments are then whole 16-byte pieces.
+#define ATT_KPERM(i) (((i) & 0x13) | (((i) & 4) << 1) | (((i) & 8) >> 1))
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+// LDS-direct load: every lane gives its own global address of 16 bytes, the wave's
+// 1 KiB lands at lds_base + 16 * lane (lds_base wave-uniform, passed in M0).
+// Issued from inline assembly so that the compiler's automatic wait insertion,
+// which cannot tell the ring slots apart, does not wait for ALL outstanding
+// loads before every LDS read; the waits for these loads are placed by hand.
+// Unknown to the compiler's counters, they can only make its own vmcnt waits
+// longer than needed, never shorter (loads complete in order).  M0 is reserved
+// by the compiler, which warns about the clobber; nothing else here uses M0.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void att_global_to_lds16(const void* gptr, const void* lds_base) {
+  const uint32_t lds_addr =
+      (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)lds_base;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(lds_addr), "v"(gptr)
+               : "memory", "m0");
+}
+#pragma clang diagnostic pop
+// s_waitcnt vmcnt(n) only / lgkmcnt(0) only.
+#define ATT_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+#define ATT_WAIT_LGKMCNT0() __builtin_amdgcn_s_waitcnt(0xC07F)
+// Workgroup barrier without the fence of __syncthreads (which would wait for
+// all outstanding LDS-direct loads, also those of the stages being prefetched).
+#define ATT_BARE_BARRIER()              \
+  asm volatile("" ::: "memory");        \
+  __builtin_amdgcn_sched_barrier(0);    \
+  __builtin_amdgcn_s_barrier();         \
+  __builtin_amdgcn_sched_barrier(0);    \
+  asm volatile("" ::: "memory")
 
 int g_attn_force_splits = 0;  // tuning knobs (0 = automatic)
-int g_attn_force_qtw = 0;
+int g_attn_force_block_tiles = 0;
 
 AttnPlan plan_attention(int B, int K, int Hq, int Hkv, int max_total_len) {
   AttnPlan p;
   int G = Hq / Hkv;
   int R = G * (K + 1);
-  int qt = (R + 15) / 16;
-  p.qtw = qt <= 8 ? 1 : (qt <= 16 ? 2 : 3);  // up to eight waves per workgroup
-  if (g_attn_force_qtw) p.qtw = g_attn_force_qtw;
-  p.nwaves = (qt + p.qtw - 1) / p.qtw;  // caller guarantees <= 8
-  int pairs = B * Hkv;
+  int qt = (R + 31) / 32;  // 32-row query tiles
+  // A workgroup holds up to eight tiles; more rows are divided evenly over
+  // several query blocks.  Up to four tiles take the key-split kernel.
+  int per_block = g_attn_force_block_tiles ? g_attn_force_block_tiles : 8;
+  p.qblocks = (qt + per_block - 1) / per_block;
+  p.block_tiles = (qt + p.qblocks - 1) / p.qblocks;
+  int wgs = B * Hkv * p.qblocks;
   int chunks = (max_total_len + ATT_KC - 1) / ATT_KC;
   if (chunks < 1) chunks = 1;
-  // one workgroup per compute unit (the kernel's registers allow no more), at
-  // least two stages per split
-  int want = g_attn_force_splits ? g_attn_force_splits : (256 + pairs - 1) / pairs;
+  // one workgroup per compute unit (the LDS ring allows no more), at least two
+  // stages per split
+  int want = g_attn_force_splits ? g_attn_force_splits : (256 + wgs - 1) / wgs;
   int maxsplit = (chunks + 1) / 2;
   if (maxsplit < 1) maxsplit = 1;
   int ns = want < maxsplit ? want : maxsplit;
@@ -61,21 +112,36 @@ size_t attention_workspace_floats(int B, int K, int Hq, int Hkv, int hd, const A
   return (size_t)B * Hkv * p.nsplit * R * (hd + 2);
 }
 
-template <int QTW, int NW>
-__global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
+// KS = 2: a wave owns (tile wave/2, key half wave%2); KS = 1: (tile wave, all keys).
+template <int KS>
+__global__ __launch_bounds__(ATT_NWAVES * 64) void attention_bf16_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ kcache, const bf16_t* __restrict__ vcache,
     const int32_t* __restrict__ kv_len, float* __restrict__ ws, int K, int Hq, int Hkv, int capacity,
-    int chunk_keys, float scale) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // 2 stages
+    int chunk_keys, int qblocks, int block_tiles, int nsplit, int npairs, float scale) {
+  __shared__ __attribute__((aligned(16))) unsigned char smem[ATT_NSTG * ATT_STAGE_BYTES];
+  constexpr int NW = ATT_NWAVES;
   constexpr int nthreads = NW * 64;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: scalar branches
-  const int g = lane >> 4, c16 = lane & 15;
-  const int split = blockIdx.x, pair = blockIdx.y, nsplit = gridDim.x;
+  const int h = lane >> 5, l32 = lane & 31;
+  constexpr int NKT = 2 / KS;  // 32-key tiles of a stage this wave multiplies
+  const int tile = KS == 2 ? wave >> 1 : wave;  // this wave's query tile
+  const int half = KS == 2 ? wave & 1 : 0;      // and key half of a stage
+  // Workgroup -> (query block, split, pair).  Workgroups are dealt to the eight
+  // XCDs (each with its own L2) round-robin by linear id; the query blocks of one
+  // (pair, split) stream the same keys, so they take consecutive slots of ONE
+  // XCD: they run together and all but the first find the keys in that L2.
+  const int xcd = blockIdx.x & 7, wslot = blockIdx.x >> 3;
+  const int qb = wslot % qblocks;
+  const int unit = (wslot / qblocks) * 8 + xcd;
+  if (unit >= nsplit * npairs) return;  // padding of the last group of eight (uniform per workgroup)
+  const int split = unit % nsplit, pair = unit / nsplit;
   const int b = pair / Hkv, kvh = pair % Hkv;
   const int G = Hq / Hkv;
   const int R = G * (K + 1);
+  const int row_begin = qb * block_tiles * 32;  // this query block's rows
+  const int row_end = min(R, row_begin + block_tiles * 32);
   const int L = kv_len[b];
   int total = L + K + 1;  // keys visible to the last query
   if (total > capacity) total = capacity;  // the host checks this bound; never read past the slab
@@ -86,262 +152,248 @@ __global__ __launch_bounds__(NW * 64) void attention_bf16_kernel(
   const bf16_t* kbase = kcache + ((int64_t)b * Hkv + kvh) * (int64_t)capacity * ATT_HD;
   const bf16_t* vbase = vcache + ((int64_t)b * Hkv + kvh) * (int64_t)ATT_HD * capacity;
 
-  // ---- this wave's query tiles: operand B of S^T = K Q^T, lane holds
-  // Q[row = 16*tile + c16][hd = 32*kk + 8g .. +8]
-  u32x4 qf[QTW][4];
-  int qrow[QTW];   // query row of this lane's column, or -1
-  int qlimit[QTW]; // number of visible keys for that row
-#pragma unroll
-  for (int t = 0; t < QTW; ++t) {
-    int r = (wave * QTW + t) * 16 + c16;
-    bool ok = r < R;
-    qrow[t] = ok ? r : -1;
-    int rc = ok ? r : R - 1;  // clamp: the load is unconditional, the value is masked
-    int i = rc / G, gq = rc % G;
-    qlimit[t] = ok ? L + i + 1 : 0;
-    const bf16_t* qp = q + ((int64_t)(b * (K + 1) + i) * Hq + kvh * G + gq) * ATT_HD;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      u32x4 v = *(const u32x4*)(qp + 32 * kk + 8 * g);
-      qf[t][kk] = ok ? v : u32x4{0u, 0u, 0u, 0u};
-    }
-  }
-
-  f32x4 oacc[QTW][8];  // O^T[hd = 16*ht + 4g + r][row c16]
-  float mrun[QTW], lrun[QTW];
-#pragma unroll
-  for (int t = 0; t < QTW; ++t) {
-    mrun[t] = -INFINITY;
-    lrun[t] = 0.f;
-#pragma unroll
-    for (int ht = 0; ht < 8; ++ht) oacc[t][ht] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
-
-  // ---- cooperative stage load: K part 64 keys x 256 B, V^T part 128 rows x 128 B,
-  // 16 bytes per thread per item; items [0, 1024) are K, [1024, 2048) are V.
-  constexpr int ITEMS = (ATT_KC * ATT_HD * 2 * 2) / 16;  // 2048
-  constexpr int MAX_PER_THREAD = ITEMS / nthreads;       // 8 (four waves) or 4 (eight waves)
-  u32x4 stgA[MAX_PER_THREAD], stgB[MAX_PER_THREAD];  // two stages in flight
-
-  // Loads are unconditional and branch-free so that all of a stage's loads are
-  // in flight together: a stage starts at a multiple of 64 below key_end and the
-  // capacity is a multiple of 64, so rows kstart..kstart+63 exist in the slab.
-  // Rows / columns at or past key_end hold whatever the allocation held
-  // (possibly NaN patterns; 0 * NaN would poison the sums): they are zeroed
-  // when the stage is written to LDS, which only the last stage needs.
-  auto load_stage = [&](u32x4 (&stg)[MAX_PER_THREAD], int kstart) {
-#pragma unroll
-    for (int it = 0; it < MAX_PER_THREAD; ++it) {
-      const int item = it * nthreads + tid;
-      if (it < MAX_PER_THREAD / 2) {  // K half (compile-time split)
-        int key = item >> 4, piece = item & 15;
-        stg[it] = *(const u32x4*)(kbase + (int64_t)(kstart + key) * ATT_HD + piece * 8);
-      } else {
-        int it2 = item - ITEMS / 2;
-        int row = it2 >> 3, piece = it2 & 7;
-        stg[it] = *(const u32x4*)(vbase + (int64_t)row * capacity + kstart + piece * 8);
-      }
-    }
-  };
-  auto store_stage = [&](const u32x4 (&stg)[MAX_PER_THREAD], int stage, int kstart) {
-    unsigned char* base = smem + stage * ATT_STAGE_BYTES;
-    const bool tail = kstart + ATT_KC > key_end;  // workgroup-uniform
-#pragma unroll
-    for (int it = 0; it < MAX_PER_THREAD; ++it) {
-      const int item = it * nthreads + tid;
-      u32x4 v = stg[it];
-      if (it < MAX_PER_THREAD / 2) {
-        int key = item >> 4, piece = item & 15;
-        if (tail && kstart + key >= key_end) v = u32x4{0u, 0u, 0u, 0u};
-        *(u32x4*)(base + key * ATT_KROW + ATT_KSWZ(key, piece)) = v;
-      } else {
-        int it2 = item - ITEMS / 2;
-        int row = it2 >> 3, piece = it2 & 7;
-        if (tail) {
-          int nvalid = key_end - (kstart + piece * 8);  // valid keys in this 8-key piece
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            uint32_t keep = (2 * w < nvalid ? 0xFFFFu : 0u) | (2 * w + 1 < nvalid ? 0xFFFF0000u : 0u);
-            v[w] &= keep;
-          }
-        }
-        *(u32x4*)(base + ATT_KC * ATT_KROW + row * ATT_VROW + ATT_VSWZ(row, piece)) = v;
-      }
-    }
-  };
-
   const int nstages = key_end > key_begin ? (key_end - key_begin + ATT_KC - 1) / ATT_KC : 0;
 
-  // One 64-key stage from LDS buffer `stage`, whose first key is kstart.
+  // ---- stage loads.  A stage is 32 wave-level LDS-direct loads of 1 KiB:
+  // loads 0..15 bring four key rows each (lane: row l/16, 16-byte piece l%16),
+  // loads 16..31 eight V^T rows each (lane: row l/8, piece l%8); the lane
+  // fetches the piece that the swizzle assigns to its LDS position.  Wave w
+  // issues loads w*LPW .. w*LPW+LPW-1.  A stage starts at a multiple of 64 below
+  // key_end and the capacity is a multiple of 64, so every address is inside
+  // the slab; keys at or past key_end hold whatever the allocation held, see
+  // the tail fix-up below.
+  constexpr int LPW = 32 / NW;
+  const bf16_t* src[LPW];
+#pragma unroll
+  for (int j = 0; j < LPW; ++j) {
+    const int ld = wave * LPW + j;
+    if (ld < 16) {
+      const int key = 4 * ld + (lane >> 4);
+      src[j] = kbase + (int64_t)(key_begin + key) * ATT_HD + ATT_KSWZ(key, lane & 15) / 2;
+    } else {
+      const int row = 8 * (ld - 16) + (lane >> 3);
+      src[j] = vbase + (int64_t)row * capacity + key_begin + ATT_VSWZ(row, lane & 7) / 2;
+    }
+  }
+  auto issue_stage = [&](int slot, int stage_idx) {
+#pragma unroll
+    for (int j = 0; j < LPW; ++j) {
+      const int ld = wave * LPW + j;
+      const int64_t adv = (ld < 16) ? (int64_t)stage_idx * ATT_KC * ATT_HD : (int64_t)stage_idx * ATT_KC;
+      att_global_to_lds16(src[j] + adv, smem + slot * ATT_STAGE_BYTES + ld * 1024);
+    }
+  };
+
+  // ---- this wave's query tile: operand B of S^T = K Q^T (32x32x16 tiles), lane
+  // holds Q[row = row_begin + 32*tile + l32][hd = 16*kk + 8h .. +8].  The loads
+  // are waited for before the first stage load is issued, so that the
+  // hand-counted waits below see stage loads only.
+  u32x4 qf[8];
+  const int qr = row_begin + tile * 32 + l32;
+  const bool row_ok = qr < row_end;
+  const int qlimit = row_ok ? L + qr / G + 1 : 0;  // number of keys visible to this row
+  {
+    const int rc = row_ok ? qr : R - 1;  // clamp: the load is unconditional, the value is masked
+    const int i = rc / G, gq = rc % G;
+    const bf16_t* qp = q + ((int64_t)(b * (K + 1) + i) * Hq + kvh * G + gq) * ATT_HD;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      u32x4 v = *(const u32x4*)(qp + 16 * kk + 8 * h);
+      qf[kk] = row_ok ? v : u32x4{0u, 0u, 0u, 0u};
+    }
+  }
+  ATT_WAIT_VMCNT(0);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int s = 0; s < ATT_NSTG - 1; ++s)
+    if (s < nstages) issue_stage(s, s);
+
+  f32x16 oacc[4];  // O^T[hd = 32*ht + 8*(r/4) + 4h + r%4][row l32], this wave's keys only
+  float mrun = -INFINITY, lrun = 0.f;
+#pragma unroll
+  for (int ht = 0; ht < 4; ++ht)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[ht][r] = 0.f;
+
+  // The wave's 32 keys of one stage (LDS buffer `stage`, first key kstart).
   //
   // Probabilities are formed relative to an INTEGER base-2 exponent n >= max s',
   // s' = (q.k) * log2(e)/sqrt(hd), n = ceil of the running maximum: when the
   // maximum grows, earlier terms are rescaled by an exact power of two, which
   // commutes with the bf16 rounding of P.  The result is the same as rounding
   // 2^(s' - n_final) once, independent of how the cache is chunked or split.
-  //
-  // The per-score vector work is what bounds this kernel once the loads are
-  // hidden, so it is kept minimal: the causal / tail mask is applied only in
-  // stages that reach past the prefix (uniform branch), the scale is folded
-  // into one fused multiply-add with the exponent, and the accumulators are
-  // rescaled only when some row's exponent actually changed.
-  const bool wave_has_rows = wave * QTW * 16 < R;
+  const bool wave_has_rows = row_begin + tile * 32 < row_end;
   auto compute_stage = [&](int stage, int kstart) {
     if (!wave_has_rows) return;  // this wave only helps with the loads
     const unsigned char* kb = smem + stage * ATT_STAGE_BYTES;
     const unsigned char* vb = kb + ATT_KC * ATT_KROW;
 
-    // S^T = K Q^T: 4 key tiles of 16; lane holds S[key = 16*kt + 4g + r][row c16].
-    // Each key fragment is read from LDS once and used for all of the wave's query tiles.
-    f32x4 sacc[QTW][4];
+    // S^T = K Q^T for the wave's key tiles; register r of tile kt in a lane is the
+    // score of key kfirst + 32*kt + 16*(r/8) + 8h + r%8 (see ATT_KPERM) and query row l32.
+    const int kfirst = kstart + half * 32;
+    f32x16 sacc[NKT];
 #pragma unroll
-    for (int t = 0; t < QTW; ++t)
+    for (int kt = 0; kt < NKT; ++kt) {
 #pragma unroll
-      for (int kt = 0; kt < 4; ++kt) sacc[t][kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int r = 0; r < 16; ++r) sacc[kt][r] = 0.f;
+      const int key = (half + kt) * 32 + ATT_KPERM(l32);
 #pragma unroll
-    for (int kt = 0; kt < 4; ++kt) {
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        u32x4 araw = *(const u32x4*)(kb + (kt * 16 + c16) * ATT_KROW + ATT_KSWZ(c16, 4 * kk + g));
-        bf16x8 a = __builtin_bit_cast(bf16x8, araw);
-#pragma unroll
-        for (int t = 0; t < QTW; ++t)
-          sacc[t][kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, __builtin_bit_cast(bf16x8, qf[t][kk]),
-                                                                sacc[t][kt], 0, 0, 0);
+      for (int kk = 0; kk < 8; ++kk) {
+        u32x4 araw = *(const u32x4*)(kb + key * ATT_KROW + ATT_KSWZ(key, 2 * kk + h));
+        sacc[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, araw),
+                                                           __builtin_bit_cast(bf16x8, qf[kk]), sacc[kt], 0, 0, 0);
       }
     }
+    if (kfirst + 32 * NKT > L + 1) {  // keys below L+1 are visible to every row (wave-uniform branch)
+#pragma unroll
+      for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          int key = kfirst + 32 * kt + 16 * (r >> 3) + 8 * h + (r & 7);
+          if (key >= qlimit) sacc[kt][r] = -INFINITY;
+        }
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+      for (int r = 0; r < 16; r += 4)
+        mx = fmaxf(mx, fmaxf(fmaxf(sacc[kt][r], sacc[kt][r + 1]), fmaxf(sacc[kt][r + 2], sacc[kt][r + 3])));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, FLY_WAVE));
+    const float mnew = fmaxf(mrun, ceilf(mx * scale));  // scale > 0: max commutes with it
+    // rows with nothing visible yet keep n = -inf; avoid inf - inf
+    const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+    if (__ballot(mnew != mrun) != 0ull) {  // wave-uniform: some row's exponent grew
+      const float corr = fast_exp2(mrun - msafe);  // exact power of two (0 when mrun = -inf)
+      lrun *= corr;
+#pragma unroll
+      for (int ht = 0; ht < 4; ++ht) oacc[ht] *= corr;
+      mrun = mnew;
+    }
+    u32x4 pb[NKT][2];  // P as operand of the P V product: 16-key steps, 8 keys per lane each
+    float lsum = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < NKT; ++kt)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        float pv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pv[e] = fast_exp2(fmaf(sacc[kt][8 * j + e], scale, -msafe));
+        lsum += ((pv[0] + pv[1]) + (pv[2] + pv[3])) + ((pv[4] + pv[5]) + (pv[6] + pv[7]));
+        pb[kt][j] = u32x4{pack_bf2_hw(pv[0], pv[1]), pack_bf2_hw(pv[2], pv[3]), pack_bf2_hw(pv[4], pv[5]),
+                          pack_bf2_hw(pv[6], pv[7])};
+      }
+    lrun += lsum;
 
-    const bool need_mask = kstart + ATT_KC > L + 1;  // keys below L+1 are visible to every row
-    uint32_t pb[QTW][4][2];  // bf16 pairs: P[key 16*kt + 4g + {0,1}], {2,3}
+    // O^T += V^T P^T.  Step (kt, j) covers 16 keys; the lane's eight keys
+    // 32*(half + kt) + 16j + 8h .. +7 are piece 4*(half + kt) + 2j + h of a V^T row.
 #pragma unroll
-    for (int t = 0; t < QTW; ++t) {
-      if (need_mask) {
+    for (int kt = 0; kt < NKT; ++kt)
 #pragma unroll
-        for (int kt = 0; kt < 4; ++kt)
+      for (int j = 0; j < 2; ++j) {
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            int key = kstart + kt * 16 + 4 * g + r;
-            if (key >= qlimit[t]) sacc[t][kt][r] = -INFINITY;
-          }
+        for (int ht = 0; ht < 4; ++ht) {
+          const int vrow = ht * 32 + l32;
+          u32x4 araw = *(const u32x4*)(vb + vrow * ATT_VROW + ATT_VSWZ(vrow, 4 * (half + kt) + 2 * j + h));
+          oacc[ht] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              __builtin_bit_cast(bf16x8, araw), __builtin_bit_cast(bf16x8, pb[kt][j]), oacc[ht], 0, 0, 0);
+        }
       }
-      float mx = -INFINITY;
-#pragma unroll
-      for (int kt = 0; kt < 4; ++kt)
-        mx = fmaxf(mx, fmaxf(fmaxf(sacc[t][kt][0], sacc[t][kt][1]), fmaxf(sacc[t][kt][2], sacc[t][kt][3])));
-      mx = fmaxf(mx, __shfl_xor(mx, 16, FLY_WAVE));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, FLY_WAVE));
-      const float mnew = fmaxf(mrun[t], ceilf(mx * scale));  // scale > 0: max commutes with it
-      // rows with nothing visible yet keep n = -inf; avoid inf - inf
-      const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
-      if (__ballot(mnew != mrun[t]) != 0ull) {  // wave-uniform: some row's exponent grew
-        const float corr = fast_exp2(mrun[t] - msafe);  // exact power of two (0 when mrun = -inf)
-        lrun[t] *= corr;
-#pragma unroll
-        for (int ht = 0; ht < 8; ++ht) oacc[t][ht] *= corr;
-        mrun[t] = mnew;
-      }
-      float lsum = 0.f;
-#pragma unroll
-      for (int kt = 0; kt < 4; ++kt) {
-        float p0 = fast_exp2(fmaf(sacc[t][kt][0], scale, -msafe));
-        float p1 = fast_exp2(fmaf(sacc[t][kt][1], scale, -msafe));
-        float p2 = fast_exp2(fmaf(sacc[t][kt][2], scale, -msafe));
-        float p3 = fast_exp2(fmaf(sacc[t][kt][3], scale, -msafe));
-        lsum += (p0 + p1) + (p2 + p3);
-        pb[t][kt][0] = pack_bf2_hw(p0, p1);
-        pb[t][kt][1] = pack_bf2_hw(p2, p3);
-      }
-      lrun[t] += lsum;
-    }
-
-    // O^T += V^T P^T.  k-step ks covers keys 32ks..32ks+31 with the operand
-    // index order (4g..4g+3 of tile 2ks, then 4g..4g+3 of tile 2ks+1); each V^T
-    // fragment is read once and used for all query tiles.
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      bf16x8 bop[QTW];
-#pragma unroll
-      for (int t = 0; t < QTW; ++t) {
-        u32x4 braw;
-        braw.x = pb[t][2 * ks][0];
-        braw.y = pb[t][2 * ks][1];
-        braw.z = pb[t][2 * ks + 1][0];
-        braw.w = pb[t][2 * ks + 1][1];
-        bop[t] = __builtin_bit_cast(bf16x8, braw);
-      }
-#pragma unroll
-      for (int ht = 0; ht < 8; ++ht) {
-        // keys 32ks + 4g .. +3 sit in piece 4ks + g/2 at byte 8(g&1); keys +16 two pieces on
-        const int vrow = ht * 16 + c16;
-        const unsigned char* vr = vb + vrow * ATT_VROW + 8 * (g & 1);
-        u32x2 lo = *(const u32x2*)(vr + ATT_VSWZ(vrow, 4 * ks + (g >> 1)));
-        u32x2 hi = *(const u32x2*)(vr + ATT_VSWZ(vrow, 4 * ks + (g >> 1) + 2));
-        u32x4 araw;
-        araw.x = lo.x;
-        araw.y = lo.y;
-        araw.z = hi.x;
-        araw.w = hi.y;
-        bf16x8 a = __builtin_bit_cast(bf16x8, araw);
-#pragma unroll
-        for (int t = 0; t < QTW; ++t)
-          oacc[t][ht] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, bop[t], oacc[t][ht], 0, 0, 0);
-      }
-    }
   };
 
-  // Pipeline: while stage i is multiplied out of LDS, stage i+1 sits in
-  // registers waiting to be written to the other LDS buffer and stage i+2 is
-  // being loaded.  Register sets alternate (A, B), LDS buffers alternate (0, 1).
-  // The steady-state loop has no conditionals so that the waits before the LDS
-  // writes cover only the older of the two register sets.
-#define KST(i) (key_begin + (i) * ATT_KC)
-  if (nstages > 0) load_stage(stgA, KST(0));
-  if (nstages > 1) load_stage(stgB, KST(1));
-  if (nstages > 0) store_stage(stgA, 0, KST(0));
-  __syncthreads();
-  int sidx = 0;
-  while (sidx + 3 < nstages) {
-    load_stage(stgA, KST(sidx + 2));
-    compute_stage(0, KST(sidx));
-    store_stage(stgB, 1, KST(sidx + 1));
-    __syncthreads();
-    load_stage(stgB, KST(sidx + 3));
-    compute_stage(1, KST(sidx + 1));
-    store_stage(stgA, 0, KST(sidx + 2));
-    __syncthreads();
-    sidx += 2;
-  }
-  for (; sidx < nstages; sidx += 2) {  // tail: at most three stages, with checks
-    if (sidx + 2 < nstages) load_stage(stgA, KST(sidx + 2));
-    compute_stage(0, KST(sidx));
-    if (sidx + 1 < nstages) store_stage(stgB, 1, KST(sidx + 1));
-    __syncthreads();
-    if (sidx + 1 >= nstages) break;
-    if (sidx + 3 < nstages) load_stage(stgB, KST(sidx + 3));
-    compute_stage(1, KST(sidx + 1));
-    if (sidx + 2 < nstages) store_stage(stgA, 0, KST(sidx + 2));
-    __syncthreads();
-  }
-#undef KST
-
-  // ---- write this split's partial: O [R, hd], m [R], l [R]
-  float* obase = ws + ((int64_t)pair * nsplit + split) * (int64_t)R * (ATT_HD + 2);
-  float* mbase = obase + (int64_t)R * ATT_HD;
-  float* lbase = mbase + R;
+  // Pipeline over the stages of this split.  Step c: wait for this wave's loads
+  // of stage c (up to two younger stages stay in flight); barrier (everyone's
+  // loads of stage c have landed, everyone is done reading stage c-1); refill
+  // the slot of stage c-1 with stage c+3; multiply stage c out of LDS.
+  int slot = 0, refill = ATT_NSTG - 1;
+  for (int c = 0; c < nstages; ++c) {
+    const int younger = min(ATT_NSTG - 2, nstages - 1 - c);  // stages issued after stage c
+    if (younger >= 2) ATT_WAIT_VMCNT(2 * LPW);
+    else if (younger == 1) ATT_WAIT_VMCNT(LPW);
+    else ATT_WAIT_VMCNT(0);
+    ATT_BARE_BARRIER();
+    if (c + ATT_NSTG - 1 < nstages) issue_stage(refill, c + ATT_NSTG - 1);
+    const int kstart = key_begin + c * ATT_KC;
+    if (kstart + ATT_KC > key_end) {
+      // Last stage of the cache: V^T columns of keys at or past key_end hold
+      // whatever the allocation held (possibly NaN patterns, and 0 * NaN would
+      // poison the sums): zero them in LDS.  Scores of such keys are replaced by
+      // -inf above, so the key rows need no such care.  Workgroup-uniform branch.
+      unsigned char* vb = smem + slot * ATT_STAGE_BYTES + ATT_KC * ATT_KROW;
+      const int nvalid_stage = key_end - kstart;  // 1..63
+      for (int item = tid; item < ATT_HD * 8; item += nthreads) {
+        const int row = item >> 3, piece = item & 7;
+        const int nvalid = nvalid_stage - piece * 8;  // valid keys in this 8-key piece
+        if (nvalid < 8) {
+          u32x4* pv = (u32x4*)(vb + row * ATT_VROW + ATT_VSWZ(row, piece));
+          u32x4 v = *pv;
 #pragma unroll
-  for (int t = 0; t < QTW; ++t) {
-    float l = lrun[t];
-    l += __shfl_xor(l, 16, FLY_WAVE);
-    l += __shfl_xor(l, 32, FLY_WAVE);
-    int r = qrow[t];
-    if (r >= 0) {
-#pragma unroll
-      for (int ht = 0; ht < 8; ++ht)
-        *(f32x4*)(obase + (int64_t)r * ATT_HD + ht * 16 + 4 * g) = oacc[t][ht];
-      if (g == 0) {
-        mbase[r] = mrun[t];
-        lbase[r] = l;
+          for (int w = 0; w < 4; ++w) {
+            uint32_t keep = (2 * w < nvalid ? 0xFFFFu : 0u) | (2 * w + 1 < nvalid ? 0xFFFF0000u : 0u);
+            v[w] &= keep;
+          }
+          *pv = v;
+        }
       }
+      __syncthreads();  // no younger stage loads are outstanding here
+    }
+    compute_stage(slot, kstart);
+    ATT_WAIT_LGKMCNT0();
+    __builtin_amdgcn_sched_barrier(0);
+    refill = slot;
+    slot = slot + 1 == ATT_NSTG ? 0 : slot + 1;
+  }
+
+  // ---- this split's partial: O [R, hd], n [R], l [R].  With split keys the two
+  // halves of each tile are first merged through LDS (the ring is free now): the
+  // odd wave hands over its O, n and l, the even wave combines them with its own
+  // (n = max of the two integer exponents, both sides rescaled by exact powers
+  // of two, the even half added first).
+  lrun += __shfl_xor(lrun, 32, FLY_WAVE);
+  float* xo = (float*)smem + tile * (16 * 4 * 64 + 64);  // [ht][r][lane] floats, then n[32], l[32]
+  float w0 = 1.f, w1 = 0.f;
+  if constexpr (KS == 2) {
+    __syncthreads();  // all stage reads done (no stage loads are outstanding after the last step)
+    if (half == 1 && wave_has_rows) {
+#pragma unroll
+      for (int ht = 0; ht < 4; ++ht)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) xo[(ht * 16 + r) * 64 + lane] = oacc[ht][r];
+      if (h == 0) {
+        xo[16 * 4 * 64 + l32] = mrun;
+        xo[16 * 4 * 64 + 32 + l32] = lrun;
+      }
+    }
+    __syncthreads();
+    if (half == 0 && wave_has_rows) {
+      const float m1 = xo[16 * 4 * 64 + l32], l1 = xo[16 * 4 * 64 + 32 + l32];
+      const float mm = fmaxf(mrun, m1);
+      const float msafe = (mm == -INFINITY) ? 0.f : mm;
+      w0 = fast_exp2(mrun - msafe);  // 0 for an empty half
+      w1 = fast_exp2(m1 - msafe);
+      lrun = lrun * w0 + l1 * w1;
+      mrun = mm;
+    }
+  }
+  if (half == 0 && row_ok) {
+    float* obase = ws + ((int64_t)pair * nsplit + split) * (int64_t)R * (ATT_HD + 2);
+    float* mbase = obase + (int64_t)R * ATT_HD;
+    float* lbase = mbase + R;
+#pragma unroll
+    for (int ht = 0; ht < 4; ++ht)
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd) {
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          v[e] = oacc[ht][4 * qd + e];
+          if constexpr (KS == 2) v[e] = v[e] * w0 + xo[(ht * 16 + 4 * qd + e) * 64 + lane] * w1;
+        }
+        *(f32x4*)(obase + (int64_t)qr * ATT_HD + ht * 32 + 8 * qd + 4 * h) = v;
+      }
+    if (h == 0) {
+      mbase[qr] = mrun;
+      lbase[qr] = lrun;
     }
   }
 }
@@ -387,28 +439,19 @@ hipError_t launch_attention_bf16(const bf16_t* q, const bf16_t* kcache, const bf
   // Shapes the kernel assumes.
   if (hd != ATT_HD || Hq % Hkv != 0 || capacity % 64 != 0 || p.chunk_keys % ATT_KC != 0)
     return hipErrorInvalidValue;
-  if (p.nwaves < 1 || p.nwaves > 8 || p.qtw < 1 || p.qtw > 3) return hipErrorInvalidValue;
   if (p.nsplit < 1 || p.nsplit > ATT_MAX_SPLITS) return hipErrorInvalidValue;
+  if (p.qblocks < 1 || p.block_tiles < 1 || p.block_tiles > 8) return hipErrorInvalidValue;
   int G = Hq / Hkv, R = G * (K + 1);
-  if (p.nwaves * p.qtw * 16 < R) return hipErrorInvalidValue;
-  // the stage loader gives each thread 2048 / nthreads items: 4 or 8 waves
-  int nw = p.nwaves <= 4 ? 4 : 8;
-  dim3 grid(p.nsplit, B * Hkv), block(nw * 64);
-  size_t smem = 2 * ATT_STAGE_BYTES;
+  if (p.qblocks * p.block_tiles * 32 < R) return hipErrorInvalidValue;
+  const int units = p.nsplit * B * Hkv;
+  dim3 grid((units + 7) / 8 * 8 * p.qblocks), block(ATT_NWAVES * 64);
   float scale = (float)(1.4426950408889634 / sqrt((double)hd));  // log2(e) / sqrt(hd)
-#define FLY_ATT_LAUNCH(QTW_, NW_)                                                                   \
-  hipLaunchKernelGGL((attention_bf16_kernel<QTW_, NW_>), grid, block, smem, st, q, kcache, vcache,   \
-                     kv_len, ws, K, Hq, Hkv, capacity, p.chunk_keys, scale)
-  if (nw == 4) {
-    if (p.qtw == 1) FLY_ATT_LAUNCH(1, 4);
-    else if (p.qtw == 2) FLY_ATT_LAUNCH(2, 4);
-    else FLY_ATT_LAUNCH(3, 4);
-  } else {
-    if (p.qtw == 1) FLY_ATT_LAUNCH(1, 8);
-    else if (p.qtw == 2) FLY_ATT_LAUNCH(2, 8);
-    else FLY_ATT_LAUNCH(3, 8);
-  }
-#undef FLY_ATT_LAUNCH
+  if (p.block_tiles <= 4)
+    hipLaunchKernelGGL(attention_bf16_kernel<2>, grid, block, 0, st, q, kcache, vcache, kv_len, ws, K, Hq,
+                       Hkv, capacity, p.chunk_keys, p.qblocks, p.block_tiles, p.nsplit, B * Hkv, scale);
+  else
+    hipLaunchKernelGGL(attention_bf16_kernel<1>, grid, block, 0, st, q, kcache, vcache, kv_len, ws, K, Hq,
+                       Hkv, capacity, p.chunk_keys, p.qblocks, p.block_tiles, p.nsplit, B * Hkv, scale);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(attention_combine_kernel, dim3(R, B * Hkv), dim3(ATT_HD), 0, st, ws, o, K, Hq, Hkv,

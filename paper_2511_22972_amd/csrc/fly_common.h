@@ -142,11 +142,12 @@ hipError_t launch_accept(const int32_t* draft, int draft_stride, const int32_t* 
 
 struct AttnPlan {
   int nsplit;      // KV splits per (sequence, kv head)
-  int qtw;         // 16-row query tiles per wave (1..3)
-  int nwaves;      // waves per workgroup
   int chunk_keys;  // keys per split (multiple of 64)
+  int qblocks;     // query-row blocks per (split, sequence, KV head): beyond 256 rows the
+                   // rows are divided over several workgroups that stream the same keys
+  int block_tiles; // 32-row tiles per query block (1..8)
 };
-extern int g_attn_force_splits, g_attn_force_qtw;
+extern int g_attn_force_splits, g_attn_force_block_tiles;
 AttnPlan plan_attention(int B, int K, int Hq, int Hkv, int max_total_len);
 size_t attention_workspace_floats(int B, int K, int Hq, int Hkv, int hd, const AttnPlan& p);
 hipError_t launch_attention_bf16(const bf16_t* q, const bf16_t* kcache, const bf16_t* vcache,

@@ -65,9 +65,10 @@ def test_workspace_query_and_shape_errors(fb):
                                       C.byref(out)) == -7
     assert fb.lib.fly_workspace_bytes(C.byref(_desc(fb, n_kv_heads=3)), 1, 4, 128, C.byref(out)) == -2
     assert fb.lib.fly_workspace_bytes(C.byref(_desc(fb, vocab=8200)), 1, 4, 128, C.byref(out)) == -2
-    # more than 384 query rows per KV head cannot be held by one workgroup
-    assert fb.lib.fly_workspace_bytes(C.byref(_desc(fb, dtype=fb.FLY_BF16, head_dim=128, n_q_heads=64,
-                                                    n_kv_heads=1)), 1, 16, 128, C.byref(out)) == -2
+    # more than 4096 query rows per KV head (17 positions x 256 heads) are refused
+    wide = dict(dtype=fb.FLY_BF16, head_dim=128, ffn=704, n_kv_heads=1)
+    assert fb.lib.fly_workspace_bytes(C.byref(_desc(fb, n_q_heads=256, **wide)), 1, 16, 128, C.byref(out)) == -2
+    assert fb.lib.fly_workspace_bytes(C.byref(_desc(fb, n_q_heads=64, **wide)), 1, 16, 128, C.byref(out)) == 0
 
 
 def test_accept_argument_checks(fb):
