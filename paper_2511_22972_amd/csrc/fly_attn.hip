@@ -413,6 +413,7 @@ __global__ __launch_bounds__(ATT_HD) void attention_combine_kernel(const float* 
   // every thread finds the largest exponent (the loads are the same for all
   // threads and independent of each other)
   float mx = -INFINITY;
+#pragma unroll 8
   for (int s = 0; s < nsplit; ++s) mx = fmaxf(mx, base[s * sstride + (int64_t)R * ATT_HD + r]);
   for (int s = e; s < nsplit; s += ATT_HD) {
     const float* sb = base + s * sstride + (int64_t)R * ATT_HD;
@@ -424,7 +425,7 @@ __global__ __launch_bounds__(ATT_HD) void attention_combine_kernel(const float* 
   __syncthreads();
   float num = 0.f, den = 0.f;
   // split order is fixed, so the sum does not depend on scheduling
-#pragma unroll 4
+#pragma unroll 8
   for (int s = 0; s < nsplit; ++s) {
     num = fmaf(base[s * sstride + (int64_t)r * ATT_HD + e], wgt[s], num);
     den += lw[s];

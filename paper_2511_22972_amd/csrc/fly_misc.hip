@@ -40,15 +40,46 @@ __global__ __launch_bounds__(RRN_THREADS) void reduce_residual_norm_kernel(
   __shared__ float wsum[RRN_THREADS / 64];
   const int m = blockIdx.x;
   float* xr = x + (int64_t)m * d;
+  // Only M rows exist, so the row is spread over 16 waves to keep enough loads
+  // in flight.  A thread owns groups of four elements RRN_THREADS*4 apart; up to
+  // RRN_KEEP of them stay in registers between the two passes.  The partials of
+  // one group are fetched four splits at a time (independent loads, one wait)
+  // and added in split order, so the sum does not depend on the batching.
+  constexpr int RRN_KEEP = 4;
+  f32x4 keep[RRN_KEEP];
   float ss = 0.f;
-  // Only M rows exist, so the row is spread over 16 waves to keep enough loads in flight.
-  for (int i = threadIdx.x * 4; i < d; i += RRN_THREADS * 4) {
+#pragma unroll
+  for (int it = 0; it < RRN_KEEP; ++it) keep[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+  auto summed = [&](int i) {
     f32x4 v = *(f32x4*)(xr + i);
-    for (int s = 0; s < splits; ++s) {
-      f32x4 p = *(const f32x4*)(partial + ((int64_t)s * M + m) * d + i);
-      v += p;
+    const float* pp = partial + (int64_t)m * d + i;
+    const int64_t sstride = (int64_t)M * d;
+    int s = 0;
+    for (; s + 4 <= splits; s += 4) {
+      f32x4 p0 = *(const f32x4*)(pp + (s + 0) * sstride);
+      f32x4 p1 = *(const f32x4*)(pp + (s + 1) * sstride);
+      f32x4 p2 = *(const f32x4*)(pp + (s + 2) * sstride);
+      f32x4 p3 = *(const f32x4*)(pp + (s + 3) * sstride);
+      v += p0;
+      v += p1;
+      v += p2;
+      v += p3;
     }
+    for (; s < splits; ++s) v += *(const f32x4*)(pp + s * sstride);
     if (splits > 0) *(f32x4*)(xr + i) = v;
+    return v;
+  };
+#pragma unroll
+  for (int it = 0; it < RRN_KEEP; ++it) {
+    const int i = (it * RRN_THREADS + threadIdx.x) * 4;
+    if (i < d) {
+      f32x4 v = summed(i);
+      keep[it] = v;
+      ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+  }
+  for (int i = (RRN_KEEP * RRN_THREADS + threadIdx.x) * 4; i < d; i += RRN_THREADS * 4) {  // very wide rows
+    f32x4 v = summed(i);
     ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
   }
   if (xn == nullptr) return;
@@ -60,11 +91,27 @@ __global__ __launch_bounds__(RRN_THREADS) void reduce_residual_norm_kernel(
   for (int w = 0; w < RRN_THREADS / 64; ++w) tot += wsum[w];
   float inv = 1.0f / sqrtf(tot / (float)d + eps);
   AT* o = xn + (int64_t)m * d;
-  for (int i = threadIdx.x * 4; i < d; i += RRN_THREADS * 4) {
-    f32x4 v = *(f32x4*)(xr + i);
+  auto emit = [&](int i, const f32x4& v) {
+    if constexpr (sizeof(AT) == 2) {
+      const u32x2 gp = *(const u32x2*)(gain + i);  // four bf16 gains
+      const float g0 = __uint_as_float(gp.x << 16), g1 = __uint_as_float(gp.x & 0xFFFF0000u);
+      const float g2 = __uint_as_float(gp.y << 16), g3 = __uint_as_float(gp.y & 0xFFFF0000u);
+      u32x2 pk;
+      pk.x = pack_bf2(v.x * inv * g0, v.y * inv * g1);
+      pk.y = pack_bf2(v.z * inv * g2, v.w * inv * g3);
+      *(u32x2*)(o + i) = pk;
+    } else {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) Act<AT>::st(o + i + e, v[e] * inv * Act<AT>::ld(gain + i + e));
+      for (int e = 0; e < 4; ++e) Act<AT>::st(o + i + e, v[e] * inv * Act<AT>::ld(gain + i + e));
+    }
+  };
+#pragma unroll
+  for (int it = 0; it < RRN_KEEP; ++it) {
+    const int i = (it * RRN_THREADS + threadIdx.x) * 4;
+    if (i < d) emit(i, keep[it]);
   }
+  for (int i = (RRN_KEEP * RRN_THREADS + threadIdx.x) * 4; i < d; i += RRN_THREADS * 4)
+    emit(i, *(f32x4*)(xr + i));
 }
 
 hipError_t launch_reduce_residual_norm(float* x, const float* partial, int splits, const void* gain,
@@ -122,11 +169,23 @@ __global__ void qkv_epilogue_kernel(const float* __restrict__ partial, int split
                                     int hd, int capacity) {
   const int m = blockIdx.x, head = blockIdx.y, e = threadIdx.x, half = hd / 2;
   const int N = (Hq + 2 * Hkv) * hd;
+  // split partials are fetched four at a time (independent loads, one wait) and
+  // added in split order
   float lo = 0.f, hi = 0.f;
-  for (int s = 0; s < splits; ++s) {
-    const float* p = partial + ((int64_t)s * M + m) * N + head * hd;
-    lo += p[e];
-    hi += p[e + half];
+  const float* p = partial + (int64_t)m * N + head * hd + e;
+  const int64_t sstride = (int64_t)M * N;
+  int s = 0;
+  for (; s + 4 <= splits; s += 4) {
+    float a0 = p[(s + 0) * sstride], b0 = p[(s + 0) * sstride + half];
+    float a1 = p[(s + 1) * sstride], b1 = p[(s + 1) * sstride + half];
+    float a2 = p[(s + 2) * sstride], b2 = p[(s + 2) * sstride + half];
+    float a3 = p[(s + 3) * sstride], b3 = p[(s + 3) * sstride + half];
+    lo += a0; lo += a1; lo += a2; lo += a3;
+    hi += b0; hi += b1; hi += b2; hi += b3;
+  }
+  for (; s < splits; ++s) {
+    lo += p[s * sstride];
+    hi += p[s * sstride + half];
   }
   const int b = m / (K + 1), i = m % (K + 1);
   if (head < Hq + Hkv) {
