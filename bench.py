@@ -26,6 +26,8 @@ import torch
 import synth
 
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = 2500.0   # dense bf16, published
+F32_PEAK_TFLOPS = 157.3     # fp32 vector / matrix, published
 # HBM bytes per launch of the dominant kernel from hardware counters (FETCH_SIZE and
 # WRITE_SIZE passes scaled by a 1 GiB copy; profiles/gateup_gemm_c3_70b_hbm_counters.md).
 MEASURED_TRAFFIC_BYTES = {"c3_70b": 946.6e6}
@@ -232,6 +234,41 @@ def main():
     gu_ms = time_region(gateup, max(args.steps, 20) * 4, 8)
     gu_bytes = cfg.d * 2 * cfg.ffn * es + cfg.M * cfg.d * es + cfg.M * cfg.ffn * es
     gu_gbs = gu_bytes / (gu_ms * 1e-3) / 1e9
+    gu_flops = 2.0 * cfg.M * cfg.d * 2 * cfg.ffn
+
+    # The LM head with its fused row statistics, timed alone the same way (GEMM
+    # kernel plus the small kernel that merges the per-block statistics).
+    hidden = synth.make_hidden(cfg, cfg.M, "cuda")
+    lm_ws = fb.alloc_workspace(fb.fly_lmhead_workspace_bytes(cfg.M, cfg.d, cfg.vocab, desc.dtype))
+    lm_out = fb.VerifyOutputs(cfg.batch, cfg.K)
+
+    def lmhead():
+        fb.fly_lmhead_entropy_argmax(hidden, model.w_lm, row_scale, cfg.vocab, lm_out.argmax.view(-1),
+                                     lm_out.p_top1.view(-1), lm_out.h_norm.view(-1), None, lm_ws)
+
+    lm_ms = time_region(lmhead, max(args.steps, 20), 4)
+    lm_bytes = cfg.d * cfg.vocab * es + cfg.M * cfg.d * es
+    lm_flops = 2.0 * cfg.M * cfg.d * cfg.vocab
+    mfma_peak = MFMA_PEAK_TFLOPS if cfg.dtype == "bf16" else F32_PEAK_TFLOPS
+    lm_head = {"avg_launch_us": lm_ms * 1e3, "flops_per_launch": lm_flops, "bytes_per_launch": lm_bytes,
+               "achieved_TFLOPs": lm_flops / (lm_ms * 1e-3) / 1e12, "achieved_GBps": lm_bytes / (lm_ms * 1e-3) / 1e9,
+               "frac_of_mfma_peak": lm_flops / (lm_ms * 1e-3) / 1e12 / mfma_peak,
+               "frac_of_hbm_peak": lm_bytes / (lm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    # Above 144 rows the GEMMs are dense contractions (LDS-tiled kernel): the
+    # dominant kernel is then the LM head and the bound is the matrix cores.
+    contraction = cfg.dtype == "bf16" and cfg.M > 144
+    if contraction:
+        roofline = {"kernel": "gemm_bf16_tiled_kernel (LM head + fused row statistics)", "bound": "mfma",
+                    "achieved": lm_head["achieved_TFLOPs"], "peak": mfma_peak, "unit": "TFLOP/s",
+                    "frac": lm_head["frac_of_mfma_peak"], "traffic": None,
+                    "flops_per_launch": lm_flops, "avg_launch_us": lm_ms * 1e3}
+    else:
+        roofline = {"kernel": "gemm_bf16_kernel (gate/up projection + SwiGLU)" if cfg.dtype == "bf16"
+                    else "gemm_f32_kernel (gate/up projection + SwiGLU)",
+                    "bound": "hbm", "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": gu_gbs / HBM_PEAK_GBS,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if not args.layers else None,
+                    "bytes_per_launch": gu_bytes, "avg_launch_us": gu_ms * 1e3}
 
     res = {
         "metric": "verified tokens/s (FLy verify step)", "value": tokens_per_s, "unit": "tokens/s",
@@ -244,12 +281,9 @@ def main():
                    "accepted_tokens_per_step": s_total},
         "step_hbm": {"algorithmic_bytes": ab["total"], "achieved_GBps": ab["total"] / (ms * 1e-3) / 1e9,
                      "frac_of_peak": ab["total"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
-        "roofline": {"kernel": "gemm_bf16_kernel (gate/up projection + SwiGLU)" if cfg.dtype == "bf16"
-                     else "gemm_f32_kernel (gate/up projection + SwiGLU)",
-                     "bound": "hbm", "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": gu_gbs / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if not args.layers else None,
-                     "bytes_per_launch": gu_bytes, "avg_launch_us": gu_ms * 1e3},
+        "roofline": roofline,
+        "gate_up": {"avg_launch_us": gu_ms * 1e3, "achieved_GBps": gu_gbs, "achieved_TFLOPs": gu_flops / (gu_ms * 1e-3) / 1e12},
+        "lm_head": lm_head,
     }
     if not args.no_cpu_baseline:
         torch.cuda.synchronize()
