@@ -254,9 +254,9 @@ def main():
                "achieved_TFLOPs": lm_flops / (lm_ms * 1e-3) / 1e12, "achieved_GBps": lm_bytes / (lm_ms * 1e-3) / 1e9,
                "frac_of_mfma_peak": lm_flops / (lm_ms * 1e-3) / 1e12 / mfma_peak,
                "frac_of_hbm_peak": lm_bytes / (lm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
-    # Above 144 rows the GEMMs are dense contractions (LDS-tiled kernel): the
+    # Above 128 rows the GEMMs are dense contractions (LDS-tiled kernel): the
     # dominant kernel is then the LM head and the bound is the matrix cores.
-    contraction = cfg.dtype == "bf16" and cfg.M > 144
+    contraction = cfg.dtype == "bf16" and cfg.M > 128
     if contraction:
         roofline = {"kernel": "gemm_bf16_tiled_kernel (LM head + fused row statistics)", "bound": "mfma",
                     "achieved": lm_head["achieved_TFLOPs"], "peak": mfma_peak, "unit": "TFLOP/s",

@@ -47,8 +47,8 @@ int splits_for(int nblocks, int nchunks) {
   return (nchunks + cps - 1) / cps;
 }
 
-// Above 144 rows the weight-streaming kernel would re-read the weights once per
-// row block; the LDS-tiled kernel takes over.  Its workgroups cover 128, 192 or
+// Above 128 rows the LDS-tiled kernel takes over (measured: already at 136 rows
+// its 192-row workgroups beat the streaming kernel's nine 16-row tiles per wave).  Its workgroups cover 128, 192 or
 // 384 rows: the shape that pads M least wins, the larger one on a tie (fewer
 // bytes staged per flop).
 GemmPlan plan_gemm_tiled(int M, int N, int Kd, bool allow_split, int forced) {
@@ -81,7 +81,7 @@ GemmPlan plan_gemm_tiled(int M, int N, int Kd, bool allow_split, int forced) {
 }
 
 GemmPlan plan_gemm(int M, int N, int Kd, bool allow_split, bool need_even_nt) {
-  if (g_tiled >= 2 || (g_tiled == 0 && M > 144)) return plan_gemm_tiled(M, N, Kd, allow_split, g_tiled);
+  if (g_tiled >= 2 || (g_tiled == 0 && M > 128)) return plan_gemm_tiled(M, N, Kd, allow_split, g_tiled);
   GemmPlan p;
   p.tiled = 0;
   const int rows_max = g_mt_max * 16;

@@ -243,7 +243,7 @@ def test_gateup_swiglu_stage_bf16():
 
 @pytest.mark.gpu
 def test_gateup_swiglu_stage_bf16_many_rows():
-    """The same stage above 144 rows, where the LDS-tiled GEMM takes over."""
+    """The same stage above 128 rows, where the LDS-tiled GEMM takes over."""
     from paper_2511_22972_amd import binding as fb
     cases = [(M, d, F, 0) for M, d, F in ((200, 128, 16 * 37), (389, 256, 1056), (145, 32, 16), (1088, 64, 512))]
     cases += [(389, 256, 1056, shape) for shape in (2, 3, 6)]
