@@ -143,6 +143,25 @@ def roofline_only(cfg, args):
     desc = fb.make_desc(cfg)
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     es = 2 if cfg.dtype == "bf16" else 4
+    if cfg.dtype == "bf16" and cfg.M > 128:
+        # contraction regime: the dominant kernel is the LM head with fused row statistics
+        w_lm = torch.empty(cfg.d * cfg.vocab, dtype=tdt, device="cuda")
+        fb.fly_pack_weight(synth.make_weight(cfg, "w_lm", -1, "cuda"), w_lm, cfg.vocab)
+        hidden = synth.make_hidden(cfg, cfg.M, "cuda")
+        row_scale = (1.0 / synth.make_row_temperature(cfg, "cuda")).reshape(-1).contiguous()
+        out = fb.VerifyOutputs(cfg.batch, cfg.K)
+        ws = fb.alloc_workspace(fb.fly_lmhead_workspace_bytes(cfg.M, cfg.d, cfg.vocab, desc.dtype))
+
+        def lmhead():
+            fb.fly_lmhead_entropy_argmax(hidden, w_lm, row_scale, cfg.vocab, out.argmax.view(-1),
+                                         out.p_top1.view(-1), out.h_norm.view(-1), None, ws)
+
+        ms = time_region(lmhead, args.steps, args.warmup)
+        flops = 2.0 * cfg.M * cfg.d * cfg.vocab
+        print(json.dumps({"kernel": "LM head + fused row statistics", "workload": cfg.name,
+                          "launches": args.steps + args.warmup, "avg_launch_us": ms * 1e3,
+                          "flops_per_launch": flops, "achieved_TFLOPs": flops / (ms * 1e-3) / 1e12}))
+        return
     packed = []
     for l in range(cfg.n_layers):
         gu = torch.empty(cfg.d * 2 * cfg.ffn, dtype=tdt, device="cuda")
