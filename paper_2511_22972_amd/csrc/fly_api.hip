@@ -33,11 +33,15 @@ int pick_mt(int rows) {
 // about one workgroup per compute unit (256), each wave holding as many column
 // strips as the register file allows (4 for up to 48 rows, else 2), so that
 // roughly 128 KiB of weight loads are in flight per compute unit.  Narrow
-// outputs reach that workgroup count by split-K; when four-strip waves would
-// need eight or more splits, two-strip waves with half the splits write less
-// partial-sum traffic and win.
+// outputs reach that workgroup count by split-K with two-strip waves (measured
+// at the 8B and 70B projection shapes: never slower than four-strip waves with
+// twice the splits, and they write half the partial sums).  A split shorter
+// than twenty 128-wide chunks spends much of its time filling the register ring:
+// then one split fewer wins even though fewer compute units are busy (output
+// projection at 70B width: 3 x 64 workgroups beat 4 x 64).
 int splits_for(int nblocks, int nchunks) {
   int s = (g_target_wgs + nblocks / 2) / nblocks;  // round to nearest
+  if (s > 2 && (nchunks + s - 1) / s < 20) s -= 1;
   int max_splits = nchunks / 4;                     // at least four 128-wide chunks per split
   if (max_splits < 1) max_splits = 1;
   if (s > max_splits) s = max_splits;
@@ -95,7 +99,7 @@ GemmPlan plan_gemm(int M, int N, int Kd, bool allow_split, bool need_even_nt) {
   if (g_force_nt) {
     nt = g_force_nt;
   } else if (allow_split) {
-    if (nt == 4 && splits_for(blocks(4), nchunks) >= 8 && splits_for(blocks(2), nchunks) <= 4) nt = 2;
+    nt = 2;
   } else {
     // no split-K possible: narrow the wave tile until the launch has enough workgroups
     while (nt > 1 && blocks(nt) < g_target_wgs * 3 / 4) nt /= 2;
