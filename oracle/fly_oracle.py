@@ -23,6 +23,18 @@ force over all mismatch/gate patterns, scipy's logsumexp/entropy, torch's
 scaled_dot_product_attention, and the Hugging Face Llama implementation run
 in fp64 on a tiny model.  Free-running parity of the full forward at bf16
 depth is pinned only up to the stated logit tolerance (see `Numerics`).
+
+  * prompt-lookup drafting     -- Sec. 2.3 names n-gram retrieval over the
+                                  context as the parameter-free drafter and gives
+                                  no parameters; the rule written out in
+                                  `pld_propose` is this build's reading.  Pinned
+                                  by an independently written search and by the
+                                  exact continuation of periodic sequences.
+  * decode loop                -- Algorithm 1's outer loop with the KV cache
+                                  rolled forward by s per round, tau = s/t
+                                  (Eq. 12).  Pinned by the fact that with the gate
+                                  always strict the output is the target's own
+                                  greedy continuation.
 """
 from __future__ import annotations
 
@@ -415,3 +427,76 @@ def verify_block(tokens, embed: torch.Tensor, layers: Sequence[LayerWeights],
     if return_logits:
         out["logits"] = logits.numpy()
     return out
+
+
+# ==========================================================================
+# 4. Drafting by prompt lookup and the decode loop (Sec. 2.3; Algorithm 1)
+# ==========================================================================
+
+def pld_propose(y: Sequence[int], n_max: int, K: int) -> Tuple[List[int], int]:
+    """K draft tokens for the sequence y by n-gram retrieval (Sec. 2.3).
+
+    The paper names the method and no parameters; the reading taken:
+      * for n = n_max, n_max-1, .., 1 look for an earlier occurrence of the last
+        n tokens of y, i.e. an end position e < len(y) with y[e-n:e] == y[-n:];
+        the longest n that occurs wins, and among its occurrences the latest;
+      * the drafts are the tokens that followed that occurrence; where the
+        continuation runs past the end of y it goes on through the drafts
+        already written (so a periodic sequence is continued periodically);
+      * without any occurrence the last token is repeated K times.
+    Returns (drafts, n) with n = 0 for "no occurrence".
+    """
+    y = [int(t) for t in y]
+    L = len(y)
+    assert L >= 1 and n_max >= 1 and K >= 1
+    for n in range(min(n_max, L - 1), 0, -1):
+        pattern = y[L - n:]
+        for e in range(L - 1, n - 1, -1):     # latest occurrence first
+            if y[e - n:e] == pattern:
+                ext = list(y)
+                for i in range(K):
+                    ext.append(ext[e + i])
+                return ext[L:], n
+    return [y[-1]] * K, 0
+
+
+def decode_rounds(y0: Sequence[int], kv0: Sequence[Tuple[torch.Tensor, torch.Tensor]],
+                  embed: torch.Tensor, layers: Sequence[LayerWeights], g_final: torch.Tensor,
+                  w_lm: torch.Tensor, row_scale: Optional[torch.Tensor], *, rounds: int, K: int,
+                  n_max: int, theta: float, W: int, n_q_heads: int, n_kv_heads: int,
+                  head_dim: int, rope_theta: float, eps: float, storage: str = "f32",
+                  drafter=None) -> Dict:
+    """Algorithm 1's loop for ONE sequence, `rounds` rounds (no end-of-sequence
+    token in the synthetic setting), with `pld_propose` as the drafter (or
+    `drafter(y, K) -> (drafts, tag)` when given: Algorithm 1 takes any M_D).
+
+    y0: the sequence so far; its last token is y_{-1}, not yet in the cache.
+    kv0[layer] = (k [L, Hkv, hd], v [L, Hkv, hd]): the cache of everything
+    before y_{-1}.  Each round keeps s = (kept drafts + 1) tokens: the cache
+    grows by the rows of (y_{-1}, kept drafts) -- the rows computed from the
+    tokens that ARE in the output, also where a kept draft differs from the
+    target's own choice -- and the correction / bonus token becomes the next
+    y_{-1}.  Returns the final sequence, s per round, tau = sum(s) / rounds
+    (Eq. 12), the per-round statistics and the final cache.
+    """
+    y = [int(t) for t in y0]
+    kv = [(k.clone(), v.clone()) for k, v in kv0]
+    trace, loose, per_round = [], [], []
+    for _ in range(rounds):
+        drafts, n = pld_propose(y, n_max, K) if drafter is None else drafter(y, K)
+        tokens = np.asarray([[y[-1]] + drafts], dtype=np.int64)
+        out = verify_block(tokens, embed, layers, g_final, w_lm,
+                           [(k[None], v[None]) for k, v in kv], row_scale,
+                           n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, head_dim=head_dim,
+                           rope_theta=rope_theta, eps=eps, theta=theta, W=W, storage=storage)
+        a = int(out["accept_len"][0])
+        s = a + 1
+        y += drafts[:a] + [int(out["next_token"][0])]
+        kv = [(torch.cat([k, nk[:s]]), torch.cat([v, nv[:s]]))
+              for (k, v), (nk, nv) in zip(kv, out["new_kv"][0])]
+        trace.append(s)
+        loose.append(int(out["n_loose"][0]))
+        per_round.append({"drafts": drafts, "ngram": n, "argmax": out["argmax"][0].copy(),
+                          "h": out["h"][0].copy(), "margin": out["margin"][0].copy()})
+    return {"y": y, "s": trace, "tau": sum(trace) / max(rounds, 1), "n_loose": loose,
+            "rounds": per_round, "kv": kv}
