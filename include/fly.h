@@ -176,6 +176,65 @@ fly_status fly_verify_block(const fly_model_desc* desc, const fly_weights* w, co
                             size_t workspace_bytes, fly_stream stream);
 
 /*
+ * The sequences of a multi-round decode (Algorithm 1: y, and the counters s, t).
+ * Row b of ctx holds y of sequence b: the prompt followed by everything emitted
+ * so far; ctx_len[b] tokens are valid.  The last token of a row is y_{-1}: it
+ * is not yet in the KV cache, so kv_len[b] == ctx_len[b] - 1 must hold on entry
+ * (the cache of a synthetic prefix may of course not be the cache of these
+ * tokens; only the lengths must agree).  All arrays [device]; statistics may
+ * be NULL and are ACCUMULATED (zero them before the first call).
+ */
+typedef struct {
+  int32_t* ctx;             /* [B, ctx_capacity] int32 */
+  int32_t* ctx_len;         /* [B] advanced by s every round */
+  int32_t* kv_len;          /* [B] the cache lengths; must be the array the fly_kv_cache points to */
+  int32_t ctx_capacity;     /* tokens per row */
+  int32_t max_ctx_len;      /* host-side bound: ctx_len[b] <= max_ctx_len on entry */
+  int64_t* accepted_total;  /* [B] sum of s over the rounds (Algorithm 1's s), nullable */
+  int32_t* rounds_done;     /* [B] Algorithm 1's t, nullable; tau = accepted_total / rounds_done (Eq. 12) */
+  int64_t* loose_total;     /* [B] mismatching drafts that were kept, nullable */
+  int32_t* accept_trace;    /* [rounds, B] s of every round of this call, nullable */
+  int32_t* ngram_trace;     /* [rounds, B] n-gram length the drafter matched (0: none), nullable */
+} fly_sequences;
+
+/*
+ * Prompt-lookup drafting (Sec. 2.3 names n-gram retrieval over the context as
+ * the parameter-free drafter; the rule is this library's).  For every sequence:
+ * the longest n <= ngram_max such that the last n tokens occur earlier in the
+ * sequence wins, among its occurrences the latest; the K tokens following it
+ * are proposed, continuing through the proposal itself where the copy runs past
+ * the end; without any occurrence the last token is repeated.
+ *   ctx [device] int32 [B, ctx_capacity], ctx_len [device] int32 [B], 1 <= ctx_len[b] <= ctx_capacity
+ *   tokens [device] int32 [B, K+1]: (last token, draft_1..draft_K), the block fly_verify_block takes
+ *   ngram  [device] int32 [B], nullable: the n that matched (0: none)
+ * 1 <= K <= 63, 1 <= ngram_max <= 64.  Integer-only, deterministic.
+ */
+fly_status fly_pld_draft(const int32_t* ctx, const int32_t* ctx_len, int32_t ctx_capacity, int32_t B,
+                         int32_t K, int32_t ngram_max, int32_t* tokens, int32_t* ngram,
+                         fly_stream stream);
+
+/*
+ * `rounds` rounds of Algorithm 1 on the device, without a host round trip:
+ * draft K tokens by prompt lookup (fly_pld_draft), verify them
+ * (fly_verify_block: forward, row statistics, loose acceptance), then append
+ * the kept drafts and the correction / bonus token to the sequences and move
+ * the cache lengths to the rows that stay valid (kv_len += s).  There is no
+ * end-of-sequence token in this setting: the loop runs the given number of
+ * rounds.  row_scale (nullable) is applied to the K+1 rows of every round.
+ * The host-side bounds must leave room for the whole call:
+ *   kv->max_kv_len + rounds*(K+1) <= kv->capacity,
+ *   seq->max_ctx_len + rounds*(K+1) <= seq->ctx_capacity,
+ * else FLY_ERR_KV_CAPACITY.  kv->kv_len must be seq->kv_len (it is written).
+ * Workspace: fly_decode_workspace_bytes(desc, B, K, kv->max_kv_len + rounds*(K+1)).
+ */
+fly_status fly_decode_workspace_bytes(const fly_model_desc* desc, int32_t B, int32_t K,
+                                      int32_t max_kv_len_end, size_t* bytes);
+fly_status fly_decode_rounds(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                             const fly_sequences* seq, const float* row_scale, int32_t B, int32_t K,
+                             float theta, int32_t W, int32_t ngram_max, int32_t rounds,
+                             void* workspace, size_t workspace_bytes, fly_stream stream);
+
+/*
  * Decoder layers [layer_begin, layer_end) applied in place to a residual
  * stream x [device] fp32 [M, d] (the middle of fly_verify_block, exposed for
  * per-layer checks and per-layer timing).  Uses the same workspace.

@@ -23,6 +23,7 @@ EXPORTS = [
     "fly_strerror", "fly_set_tuning", "fly_packed_weight_bytes", "fly_pack_weight",
     "fly_workspace_bytes", "fly_lmhead_workspace_bytes", "fly_verify_block", "fly_decoder_layers",
     "fly_lmhead_entropy_argmax", "fly_accept", "fly_attention", "fly_gateup_swiglu", "fly_proj_partial",
+    "fly_pld_draft", "fly_decode_workspace_bytes", "fly_decode_rounds",
 ]
 
 
@@ -60,6 +61,13 @@ class fly_verify_out(C.Structure):
                 ("lse", C.c_void_p), ("n_loose", C.c_void_p), ("hidden_out", C.c_void_p)]
 
 
+class fly_sequences(C.Structure):
+    _fields_ = [("ctx", C.c_void_p), ("ctx_len", C.c_void_p), ("kv_len", C.c_void_p),
+                ("ctx_capacity", C.c_int32), ("max_ctx_len", C.c_int32),
+                ("accepted_total", C.c_void_p), ("rounds_done", C.c_void_p), ("loose_total", C.c_void_p),
+                ("accept_trace", C.c_void_p), ("ngram_trace", C.c_void_p)]
+
+
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(
@@ -95,6 +103,14 @@ def _load() -> C.CDLL:
                                       C.c_int32, C.c_int32, C.c_void_p]
     lib.fly_proj_partial.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                      C.c_int32, C.POINTER(C.c_int32), C.c_size_t, C.c_void_p]
+    lib.fly_pld_draft.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                  C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.fly_decode_workspace_bytes.argtypes = [C.POINTER(fly_model_desc), C.c_int32, C.c_int32, C.c_int32,
+                                               C.POINTER(C.c_size_t)]
+    lib.fly_decode_rounds.argtypes = [C.POINTER(fly_model_desc), C.POINTER(fly_weights),
+                                      C.POINTER(fly_kv_cache), C.POINTER(fly_sequences), C.c_void_p,
+                                      C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_int32,
+                                      C.c_void_p, C.c_size_t, C.c_void_p]
     for name in EXPORTS:
         if name != "fly_strerror":
             getattr(lib, name).restype = C.c_int
@@ -310,6 +326,64 @@ def fly_verify_block(model: PackedModel, kv: KVCache, tokens: torch.Tensor,
                                 _ptr(tokens), _ptr(row_scale), B, R - 1, theta, W, C.byref(outs),
                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
                                 _stream()), "fly_verify_block")
+
+
+class Sequences:
+    """Device buffers of a multi-round decode: token rows, their lengths and the statistics."""
+
+    def __init__(self, kv: KVCache, ctx_capacity: int, rounds: int, device="cuda"):
+        B = kv.B
+        self.kv, self.B, self.ctx_capacity, self.rounds = kv, B, ctx_capacity, rounds
+        self.ctx = torch.zeros(B, ctx_capacity, dtype=torch.int32, device=device)
+        self.ctx_len = torch.zeros(B, dtype=torch.int32, device=device)
+        self.max_ctx_len = 0
+        self.accepted_total = torch.zeros(B, dtype=torch.int64, device=device)
+        self.rounds_done = torch.zeros(B, dtype=torch.int32, device=device)
+        self.loose_total = torch.zeros(B, dtype=torch.int64, device=device)
+        self.accept_trace = torch.zeros(max(rounds, 1), B, dtype=torch.int32, device=device)
+        self.ngram_trace = torch.zeros(max(rounds, 1), B, dtype=torch.int32, device=device)
+
+    def set_sequences(self, rows) -> None:
+        """rows: one token list per sequence; also sets the cache lengths to len - 1."""
+        lens = [len(r) for r in rows]
+        for b, r in enumerate(rows):
+            self.ctx[b, :len(r)] = torch.as_tensor(r, dtype=torch.int32)
+        self.ctx_len.copy_(torch.as_tensor(lens, dtype=torch.int32))
+        self.max_ctx_len = max(lens)
+        self.kv.set_lengths([n - 1 for n in lens])
+
+    def struct(self) -> fly_sequences:
+        return fly_sequences(self.ctx.data_ptr(), self.ctx_len.data_ptr(), self.kv.kv_len.data_ptr(),
+                             self.ctx_capacity, self.max_ctx_len, self.accepted_total.data_ptr(),
+                             self.rounds_done.data_ptr(), self.loose_total.data_ptr(),
+                             self.accept_trace.data_ptr(), self.ngram_trace.data_ptr())
+
+
+def fly_pld_draft(ctx: torch.Tensor, ctx_len: torch.Tensor, K: int, ngram_max: int, tokens: torch.Tensor,
+                  ngram: Optional[torch.Tensor]) -> None:
+    B, cap = ctx.shape
+    _check(lib.fly_pld_draft(_ptr(ctx), _ptr(ctx_len), cap, B, K, ngram_max, _ptr(tokens), _ptr(ngram),
+                             _stream()), "fly_pld_draft")
+
+
+def fly_decode_workspace_bytes(desc: fly_model_desc, B: int, K: int, max_kv_len_end: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib.fly_decode_workspace_bytes(C.byref(desc), B, K, max_kv_len_end, C.byref(out)),
+           "fly_decode_workspace_bytes")
+    return out.value
+
+
+def fly_decode_rounds(model: PackedModel, kv: KVCache, seq: Sequences, row_scale: Optional[torch.Tensor],
+                      K: int, theta: float, W: int, ngram_max: int, rounds: int,
+                      workspace: torch.Tensor) -> None:
+    """Runs `rounds` rounds; afterwards the host-side bounds of `kv` and `seq` are moved along."""
+    kvs, ss = kv.struct(), seq.struct()
+    _check(lib.fly_decode_rounds(C.byref(model.desc), C.byref(model.weights_c), C.byref(kvs), C.byref(ss),
+                                 _ptr(row_scale), kv.B, K, theta, W, ngram_max, rounds, _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream()),
+           "fly_decode_rounds")
+    kv.max_kv_len += rounds * (K + 1)
+    seq.max_ctx_len += rounds * (K + 1)
 
 
 def fly_decoder_layers(model: PackedModel, kv: KVCache, x: torch.Tensor, layer_begin: int,

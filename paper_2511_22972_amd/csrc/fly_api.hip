@@ -316,6 +316,53 @@ fly_status run_layers(const fly_model_desc* desc, const fly_weights* w, const fl
   return FLY_OK;
 }
 
+// The step itself on a carved workspace (arguments already validated).
+fly_status run_verify(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                      const int32_t* tokens, const float* row_scale, int B, int K, float theta, int W,
+                      const fly_verify_out* out, const Workspace& ws, const Plans& pl, hipStream_t st) {
+  const int M = B * (K + 1), d = desc->d, dt = desc->dtype;
+  HIP_TRY(launch_rope_table(kv->kv_len, ws.rope, B, K, desc->head_dim, desc->rope_theta, st));
+  HIP_TRY(launch_embed(tokens, w->embed, dt, ws.x, M, d, desc->vocab, st));
+  const void* first_gain = desc->n_layers > 0 ? w->layers[0].g_attn : w->g_final;
+  HIP_TRY(launch_reduce_residual_norm(ws.x, nullptr, 0, first_gain, ws.xn, dt, M, d, desc->rms_eps, st));
+  FLY_TRY(run_layers(desc, w, kv, ws, pl, 0, desc->n_layers, B, K, st));
+  if (out->hidden_out)
+    HIP_TRY(hipMemcpyAsync(out->hidden_out, ws.x, (size_t)M * d * 4, hipMemcpyDeviceToDevice, st));
+  // LM head with fused statistics: logits stay in registers
+  FLY_TRY(run_gemm(dt, ws.xn, w->w_lm, ws.lm_partial, row_scale, M, desc->vocab, d, pl.lm, EPI_LMHEAD, st));
+  HIP_TRY(launch_lmhead_combine(ws.lm_partial, pl.lm_parts, M, desc->vocab, out->argmax, out->p_top1,
+                                out->h_norm, out->lse, st));
+  // acceptance rule on (draft, argmax, h)
+  HIP_TRY(launch_accept(tokens + 1, K + 1, out->argmax, out->h_norm, kv->kv_len, B, K, theta, W,
+                        out->accept_len, out->next_token, out->n_loose, out->kv_len_out, st));
+  return FLY_OK;
+}
+
+// Per-round buffers of the decode loop (behind the verification workspace).
+struct DecodeScratch {
+  int32_t *tokens, *accept_len, *next_token, *kv_len_out, *argmax, *n_loose;
+  float *h_norm, *p_top1;
+  size_t bytes;
+};
+void carve_decode(int B, int K, void* base, DecodeScratch* ds) {
+  const size_t M = (size_t)B * (K + 1);
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    void* p = base ? (void*)((char*)base + off) : nullptr;
+    off += round_up(bytes, 256);
+    return p;
+  };
+  ds->tokens = (int32_t*)take(M * 4);
+  ds->accept_len = (int32_t*)take((size_t)B * 4);
+  ds->next_token = (int32_t*)take((size_t)B * 4);
+  ds->kv_len_out = (int32_t*)take((size_t)B * 4);
+  ds->n_loose = (int32_t*)take((size_t)B * 4);
+  ds->argmax = (int32_t*)take(M * 4);
+  ds->h_norm = (float*)take(M * 4);
+  ds->p_top1 = (float*)take(M * 4);
+  ds->bytes = off;
+}
+
 }  // namespace
 
 extern "C" {
@@ -549,23 +596,78 @@ fly_status fly_verify_block(const fly_model_desc* desc, const fly_weights* w, co
   if (!workspace || workspace_bytes < ws.bytes) return FLY_ERR_WORKSPACE;
   if (!aligned16(workspace)) return FLY_ERR_ALIGNMENT;
   carve(desc, B, K, pl, workspace, &ws);
+  return run_verify(desc, w, kv, tokens, row_scale, B, K, theta, W, out, ws, pl, (hipStream_t)stream);
+}
 
+fly_status fly_pld_draft(const int32_t* ctx, const int32_t* ctx_len, int32_t ctx_capacity, int32_t B,
+                         int32_t K, int32_t ngram_max, int32_t* tokens, int32_t* ngram,
+                         fly_stream stream) {
+  if (!ctx || !ctx_len || !tokens) return FLY_ERR_NULL_POINTER;
+  FLY_TRY(check_block(B, K));
+  if (ctx_capacity < 1 || ngram_max < 1 || ngram_max > 64) return FLY_ERR_BAD_SHAPE;
+  HIP_TRY(launch_pld_draft(ctx, ctx_len, ctx_capacity, B, K, ngram_max, tokens, ngram, (hipStream_t)stream));
+  return FLY_OK;
+}
+
+fly_status fly_decode_workspace_bytes(const fly_model_desc* desc, int32_t B, int32_t K,
+                                      int32_t max_kv_len_end, size_t* bytes) {
+  if (!bytes) return FLY_ERR_NULL_POINTER;
+  FLY_TRY(check_desc(desc));
+  FLY_TRY(check_block(B, K));
+  if (max_kv_len_end < 0) return FLY_ERR_BAD_SHAPE;
+  Plans pl;
+  FLY_TRY(make_plans(desc, B, K, max_kv_len_end, &pl));
+  Workspace ws;
+  carve(desc, B, K, pl, nullptr, &ws);
+  DecodeScratch ds;
+  carve_decode(B, K, nullptr, &ds);
+  *bytes = ws.bytes + ds.bytes;
+  return FLY_OK;
+}
+
+fly_status fly_decode_rounds(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                             const fly_sequences* seq, const float* row_scale, int32_t B, int32_t K,
+                             float theta, int32_t W, int32_t ngram_max, int32_t rounds,
+                             void* workspace, size_t workspace_bytes, fly_stream stream) {
+  FLY_TRY(check_desc(desc));
+  FLY_TRY(check_block(B, K));
+  if (W < 0) return FLY_ERR_WINDOW;
+  if (theta != theta) return FLY_ERR_THETA;
+  if (!seq || !seq->ctx || !seq->ctx_len || !seq->kv_len) return FLY_ERR_NULL_POINTER;
+  if (rounds < 0 || ngram_max < 1 || ngram_max > 64 || seq->ctx_capacity < 1 || seq->max_ctx_len < 1)
+    return FLY_ERR_BAD_SHAPE;
+  FLY_TRY(check_weights(desc, w, 0, desc->n_layers, true));
+  FLY_TRY(check_kv(desc, kv, K, 0, desc->n_layers));
+  if (kv->kv_len != seq->kv_len) return FLY_ERR_BAD_SHAPE;
+  const int64_t grow = (int64_t)rounds * (K + 1);
+  if ((int64_t)kv->max_kv_len + grow > kv->capacity) return FLY_ERR_KV_CAPACITY;
+  if ((int64_t)seq->max_ctx_len + grow > seq->ctx_capacity) return FLY_ERR_KV_CAPACITY;
+  // one plan for the whole call, made for the longest cache the call can reach
+  fly_kv_cache kvr = *kv;
+  kvr.max_kv_len = kv->max_kv_len + (int32_t)(rounds > 0 ? grow - (K + 1) : 0);
+  Plans pl;
+  FLY_TRY(make_plans(desc, B, K, kv->max_kv_len + (int32_t)grow, &pl));
+  Workspace ws;
+  carve(desc, B, K, pl, nullptr, &ws);
+  DecodeScratch ds;
+  carve_decode(B, K, nullptr, &ds);
+  if (!workspace || workspace_bytes < ws.bytes + ds.bytes) return FLY_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return FLY_ERR_ALIGNMENT;
+  carve(desc, B, K, pl, workspace, &ws);
+  carve_decode(B, K, (char*)workspace + ws.bytes, &ds);
+  fly_verify_out out{ds.accept_len, ds.next_token, ds.kv_len_out, ds.argmax, ds.h_norm, ds.p_top1,
+                     nullptr, ds.n_loose, nullptr};
   hipStream_t st = (hipStream_t)stream;
-  const int M = B * (K + 1), d = desc->d, dt = desc->dtype;
-  HIP_TRY(launch_rope_table(kv->kv_len, ws.rope, B, K, desc->head_dim, desc->rope_theta, st));
-  HIP_TRY(launch_embed(tokens, w->embed, dt, ws.x, M, d, desc->vocab, st));
-  const void* first_gain = desc->n_layers > 0 ? w->layers[0].g_attn : w->g_final;
-  HIP_TRY(launch_reduce_residual_norm(ws.x, nullptr, 0, first_gain, ws.xn, dt, M, d, desc->rms_eps, st));
-  FLY_TRY(run_layers(desc, w, kv, ws, pl, 0, desc->n_layers, B, K, st));
-  if (out->hidden_out)
-    HIP_TRY(hipMemcpyAsync(out->hidden_out, ws.x, (size_t)M * d * 4, hipMemcpyDeviceToDevice, st));
-  // LM head with fused statistics: logits stay in registers
-  FLY_TRY(run_gemm(dt, ws.xn, w->w_lm, ws.lm_partial, row_scale, M, desc->vocab, d, pl.lm, EPI_LMHEAD, st));
-  HIP_TRY(launch_lmhead_combine(ws.lm_partial, pl.lm_parts, M, desc->vocab, out->argmax, out->p_top1,
-                                out->h_norm, out->lse, st));
-  // acceptance rule on (draft, argmax, h)
-  HIP_TRY(launch_accept(tokens + 1, K + 1, out->argmax, out->h_norm, kv->kv_len, B, K, theta, W,
-                        out->accept_len, out->next_token, out->n_loose, out->kv_len_out, st));
+  for (int r = 0; r < rounds; ++r) {
+    int32_t* ngram_row = seq->ngram_trace ? seq->ngram_trace + (int64_t)r * B : nullptr;
+    int32_t* trace_row = seq->accept_trace ? seq->accept_trace + (int64_t)r * B : nullptr;
+    HIP_TRY(launch_pld_draft(seq->ctx, seq->ctx_len, seq->ctx_capacity, B, K, ngram_max, ds.tokens,
+                             ngram_row, st));
+    FLY_TRY(run_verify(desc, w, &kvr, ds.tokens, row_scale, B, K, theta, W, &out, ws, pl, st));
+    HIP_TRY(launch_roll_forward(seq->ctx, seq->ctx_len, seq->kv_len, seq->ctx_capacity, B, K, ds.tokens,
+                                ds.accept_len, ds.next_token, ds.kv_len_out, ds.n_loose,
+                                seq->accepted_total, seq->rounds_done, seq->loose_total, trace_row, st));
+  }
   return FLY_OK;
 }
 

@@ -156,3 +156,12 @@ hipError_t launch_attention_bf16(const bf16_t* q, const bf16_t* kcache, const bf
 hipError_t launch_attention_f32(const float* q, const float* kcache, const float* vcache,
                                 const int32_t* kv_len, float* o, int B, int K, int Hq, int Hkv,
                                 int hd, int capacity, hipStream_t st);
+
+// Decode loop (prompt-lookup drafter, end-of-round bookkeeping).
+hipError_t launch_pld_draft(const int32_t* ctx, const int32_t* ctx_len, int ctx_capacity, int B, int K,
+                            int n_max, int32_t* tokens, int32_t* ngram, hipStream_t st);
+hipError_t launch_roll_forward(int32_t* ctx, int32_t* ctx_len, int32_t* kv_len, int ctx_capacity, int B,
+                               int K, const int32_t* tokens, const int32_t* accept_len,
+                               const int32_t* next_token, const int32_t* kv_len_out,
+                               const int32_t* n_loose, int64_t* accepted_total, int32_t* rounds_done,
+                               int64_t* loose_total, int32_t* trace_row, hipStream_t st);

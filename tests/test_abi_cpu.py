@@ -148,3 +148,44 @@ def test_pack_argument_checks(fb):
     assert f(p, 64, 32, 1, p, 32, 1, 1, None) == -2      # last tile would fall outside dst
     assert f(p, 64, 32, 1, p, 64, 2, 2, None) == -2      # tiles 2 and 4 of a 4-tile destination
     assert f(p, 64, 32, 9, p, 32, 0, 1, None) == -6
+
+
+def test_decode_argument_checks(fb):
+    p = C.c_void_p(4096)
+    f = fb.lib.fly_pld_draft
+    assert f(None, p, 64, 2, 4, 3, p, None, None) == -1
+    assert f(p, p, 64, 2, 4, 3, None, None, None) == -1
+    assert f(p, p, 64, 0, 4, 3, p, None, None) == -2
+    assert f(p, p, 64, 2, 64, 3, p, None, None) == -3
+    assert f(p, p, 64, 2, 4, 0, p, None, None) == -2
+    assert f(p, p, 64, 2, 4, 65, p, None, None) == -2
+    assert f(p, p, 0, 2, 4, 3, p, None, None) == -2
+    out = C.c_size_t(0)
+    d = _desc(fb)
+    assert fb.lib.fly_decode_workspace_bytes(C.byref(d), 2, 4, 256, C.byref(out)) == 0
+    ws = C.c_size_t(0)
+    fb.lib.fly_workspace_bytes(C.byref(d), 2, 4, 256, C.byref(ws))
+    assert out.value > ws.value                                    # verification workspace + round buffers
+    assert fb.lib.fly_decode_workspace_bytes(C.byref(d), 2, 4, 256, None) == -1
+    lw = (fb.fly_layer_weights * 2)(*[fb.fly_layer_weights(4096, 4096, 4096, 4096, 4096, 4096)] * 2)
+    w = fb.fly_weights(4096, lw, 4096, 4096)
+    karr = (C.c_void_p * 2)(4096, 4096)
+    kv = fb.fly_kv_cache(karr, karr, 4096, 192, 100)
+    seq = fb.fly_sequences(4096, 4096, 4096, 256, 101, None, None, None, None, None)
+    g = fb.lib.fly_decode_rounds
+    args = lambda **kw: [C.byref(d), C.byref(w), kw.get("kv", C.byref(kv)), kw.get("seq", C.byref(seq)), None,
+                         2, kw.get("K", 4), kw.get("theta", 0.3), kw.get("W", 6), kw.get("n", 3),
+                         kw.get("rounds", 3), kw.get("ws", 4096), kw.get("wsb", out.value), None]
+    assert g(*args(seq=None)) == -1
+    assert g(*args(K=0)) == -3
+    assert g(*args(W=-1)) == -4
+    assert g(*args(theta=float("nan"))) == -5
+    assert g(*args(n=0)) == -2
+    assert g(*args(rounds=-1)) == -2
+    assert g(*args(rounds=19)) == -10                               # 100 + 19*5 rows do not fit 192
+    seq_small = fb.fly_sequences(4096, 4096, 4096, 110, 101, None, None, None, None, None)
+    assert g(*args(seq=C.byref(seq_small))) == -10                  # 101 + 15 tokens do not fit 110
+    seq_other = fb.fly_sequences(4096, 4096, 8192, 256, 101, None, None, None, None, None)
+    assert g(*args(seq=C.byref(seq_other))) == -2                   # cache lengths must be one array
+    assert g(*args(ws=None)) == -9
+    assert g(*args(wsb=out.value - 1)) == -9
