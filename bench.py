@@ -26,6 +26,9 @@ import torch
 import synth
 
 HBM_PEAK_GBS = 8000.0
+DECODE_ROUNDS = 8           # rounds of the decode-loop line (Algorithm 1 with prompt-lookup drafting)
+DECODE_WARMUP = 2
+DECODE_NGRAM = 3
 MFMA_PEAK_TFLOPS = 2500.0   # dense bf16, published
 F32_PEAK_TFLOPS = 157.3     # fp32 vector / matrix, published
 # HBM bytes per launch of the dominant kernel from hardware counters (FETCH_SIZE and
@@ -43,7 +46,8 @@ def build_gpu_workload(cfg):
     desc = fb.make_desc(cfg)
     model = fb.PackedModel(desc, lambda name, layer: synth.make_weight(cfg, name, layer, "cuda"))
     log(f"[bench] weights generated and packed in {time.time() - t0:.1f}s")
-    cap = (cfg.kv_len + cfg.K + 1 + 63) // 64 * 64
+    # room for the verified block and for the rounds of the decode-loop line
+    cap = (cfg.kv_len + (DECODE_ROUNDS + DECODE_WARMUP + 1) * (cfg.K + 1) + 63) // 64 * 64
     kv = fb.KVCache(desc, cfg.batch, cap)
     for l in range(cfg.n_layers):
         k, v = synth.make_kv_prefix(cfg, l, "cuda")
@@ -72,6 +76,38 @@ def device_draft_chain(fb, cfg, model, kv, ws, row_scale):
         tokens[:, i] = torch.where(u[:, i - 1] < cfg.p_match, y, alt[:, i - 1])
     torch.cuda.synchronize()
     return tokens
+
+
+def decode_loop_line(fb, cfg, desc, model, kv, row_scale):
+    """Algorithm 1's loop on the device: DECODE_ROUNDS rounds of (prompt-lookup
+    draft, verification step, roll-forward), timed as one region.  The prompt is
+    synthetic (seeded tokens; the cached prefix is the synthetic one, not the
+    cache of these tokens), so tau says nothing about real text: the line shows
+    what a round costs beyond the verification step."""
+    B, K = cfg.batch, cfg.K
+    n0 = cfg.kv_len + 1
+    total_rounds = DECODE_ROUNDS + DECODE_WARMUP
+    seq = fb.Sequences(kv, n0 + total_rounds * (K + 1) + 1, total_rounds)
+    prompt = synth.hash_tokens(cfg.seed, 950, B * n0, cfg.vocab, "cuda").view(B, n0)
+    prompt[:, -1] = synth.make_first_tokens(cfg, "cuda")
+    seq.ctx[:, :n0] = prompt
+    seq.ctx_len.fill_(n0)
+    seq.max_ctx_len = n0
+    ws = fb.alloc_workspace(fb.fly_decode_workspace_bytes(desc, B, K, cfg.kv_len + total_rounds * (K + 1)))
+    fb.fly_decode_rounds(model, kv, seq, row_scale, K, cfg.theta, cfg.window, DECODE_NGRAM, DECODE_WARMUP, ws)
+    torch.cuda.synchronize()
+    s_before = seq.accepted_total.sum().item()
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    fb.fly_decode_rounds(model, kv, seq, row_scale, K, cfg.theta, cfg.window, DECODE_NGRAM, DECODE_ROUNDS, ws)
+    t1.record()
+    torch.cuda.synchronize()
+    ms = t0.elapsed_time(t1)
+    s_sum = seq.accepted_total.sum().item() - s_before
+    kv.set_lengths([cfg.kv_len] * B)             # back to the state the other lines assume
+    return {"rounds": DECODE_ROUNDS, "ms_per_round": ms / DECODE_ROUNDS,
+            "tokens_per_s": s_sum / (ms * 1e-3), "tau": s_sum / (DECODE_ROUNDS * B),
+            "ngram_max": DECODE_NGRAM, "drafter": "prompt lookup on a synthetic prompt"}
 
 
 def algorithmic_bytes(cfg):
@@ -303,6 +339,7 @@ def main():
         "roofline": roofline,
         "gate_up": {"avg_launch_us": gu_ms * 1e3, "achieved_GBps": gu_gbs, "achieved_TFLOPs": gu_flops / (gu_ms * 1e-3) / 1e12},
         "lm_head": lm_head,
+        "decode_loop": decode_loop_line(fb, cfg, desc, model, kv, row_scale),
     }
     if not args.no_cpu_baseline:
         torch.cuda.synchronize()
