@@ -128,7 +128,7 @@ const char* fly_strerror(fly_status s);
  *   "gemm_splits"  split-K factor of the projections: 1..16; 0 = automatic
  *   "gemm_mt_max"  most 16-row activation tiles one workgroup holds: 5 or 9 (default 9)
  *   "gemm_tiled"   0 = the LDS-tiled GEMM above 128 rows (automatic), 1 = never,
- *                  2, 3 or 6 = always, with workgroups of 128, 192 or 384 rows
+ *                  2, 3, 4 or 6 = always, with workgroups of 128, 192, 256 or 384 rows
  *   "attn_splits"  cache splits per (sequence, KV head): 1..256; 0 = automatic
  *   "attn_block_tiles"  most 32-row query tiles per workgroup: 1..8; 0 = automatic (8)
  *   "target_wgs"   workgroups a launch aims for (default 256, one per compute unit)

@@ -13,7 +13,7 @@ int g_force_nt = 0;
 int g_force_splits = 0;
 int g_target_wgs = 256;
 int g_mt_max = 9;
-int g_tiled = 0;  // 0 automatic, 1 never, 2, 3 or 6: always, with that workgroup shape
+int g_tiled = 0;  // 0 automatic, 1 never, 2, 3, 4 or 6: always, with that workgroup shape
 
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 
@@ -52,8 +52,8 @@ int splits_for(int nblocks, int nchunks) {
 }
 
 // Above 128 rows the LDS-tiled kernel takes over (measured: already at 136 rows
-// its 192-row workgroups beat the streaming kernel's nine 16-row tiles per wave).  Its workgroups cover 128, 192 or
-// 384 rows: the shape that pads M least wins, the larger one on a tie (fewer
+// its 192-row workgroups beat the streaming kernel's nine 16-row tiles per wave).  Its workgroups cover 128, 192,
+// 256 or 384 rows: the shape that pads M least wins, the larger one on a tie (fewer
 // bytes staged per flop).
 GemmPlan plan_gemm_tiled(int M, int N, int Kd, bool allow_split, int forced) {
   GemmPlan p{1, 1, 1, 1, 3};
@@ -66,6 +66,7 @@ GemmPlan plan_gemm_tiled(int M, int N, int Kd, bool allow_split, int forced) {
   } else {
     p.tiled = 2;
     if (padded(3) <= padded(p.tiled)) p.tiled = 3;
+    if (padded(4) <= padded(p.tiled)) p.tiled = 4;
     if (padded(6) <= padded(p.tiled)) p.tiled = 6;
   }
   p.mblocks = padded(p.tiled) / gemm_bf16_tiled_rows(p.tiled);

@@ -91,7 +91,7 @@ struct GemmPlan {
   int splits;  // split-K factor (partial results go to the workspace)
   int mblocks; // row blocks (activations beyond 144 rows re-stream the weights)
   int tiled;   // 0: weight-streaming kernel (mt, nt as above); else the LDS-tiled kernel with
-               // workgroups of 256 columns x 128 (2), 192 (3) or 384 (6) rows (mt, nt unused)
+               // workgroups of 256 columns x 128 (2), 192 (3), 256 (4) or 384 (6) rows (mt, nt unused)
 };
 
 enum GemmEpilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_LMHEAD = 2 };

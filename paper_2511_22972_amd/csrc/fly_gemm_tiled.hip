@@ -295,7 +295,8 @@ __global__ __launch_bounds__(WGN* WGM * 64) void gemm_bf16_tiled_kernel(
 template <int WGN, int WGM, int WM>
 static hipError_t launch_tiled_shape(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale,
                                      int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st) {
-  constexpr int NS = WGN * WGM == 4 ? 4 : 3;
+  constexpr int STAGE_KIB = 8 * WGN + 2 * WM * WGM;   // one k-step of the workgroup tile
+  constexpr int NS = 4 * STAGE_KIB <= 144 ? 4 : 3;      // ring depth that fits the 160 KiB of LDS
   const int nblocks = (N / 16 + 8 * WGN - 1) / (8 * WGN);
   const int ktiles = Kd / 32;
   const int kps = (ktiles + plan.splits - 1) / plan.splits;
@@ -327,13 +328,16 @@ hipError_t launch_gemm_bf16_tiled(const bf16_t* X, const bf16_t* Wp, void* out, 
   switch (plan.tiled) {
     case 2: return launch_tiled_shape<2, 2, 2>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
     case 3: return launch_tiled_shape<2, 2, 3>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+    case 4: return launch_tiled_shape<2, 4, 2>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
     case 6: return launch_tiled_shape<2, 4, 3>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
   }
   return hipErrorInvalidValue;
 }
 
 // Rows and columns a workgroup of shape `tiled` covers (0 if the shape does not exist).
-int gemm_bf16_tiled_rows(int tiled) { return tiled == 2 ? 128 : tiled == 3 ? 192 : tiled == 6 ? 384 : 0; }
+int gemm_bf16_tiled_rows(int tiled) {
+  return tiled == 2 ? 128 : tiled == 3 ? 192 : tiled == 4 ? 256 : tiled == 6 ? 384 : 0;
+}
 int gemm_bf16_tiled_cols(int tiled) { return gemm_bf16_tiled_rows(tiled) ? 256 : 0; }
 
 int gemm_bf16_tiled_lmhead_parts(int N, int tiled) {

@@ -95,6 +95,21 @@ CONFIGS: Dict[str, VerifyConfig] = {
         name="c5_stress", n_layers=1, d=8192, n_q_heads=64, n_kv_heads=8, head_dim=128,
         ffn=28672, vocab=128256, dtype="bf16", batch=64, K=16, kv_len=32768,
         p_match=0.5, temperatures=(0.1, 10.0)),
+    # The paper's own block sizes (Implementation Details: K=15 for the 70B target,
+    # K=25 for the 405B one, batch 1) and the largest batch of its serving table
+    # (batch 16).  The prompt length is not stated there: 1024 cached tokens.
+    "p70b_k15": VerifyConfig(
+        name="p70b_k15", n_layers=80, d=8192, n_q_heads=64, n_kv_heads=8, head_dim=128,
+        ffn=28672, vocab=128256, dtype="bf16", batch=1, K=15, kv_len=1024, p_match=0.7,
+        temperatures=(0.3, 1.0, 3.0)),
+    "p70b_k15_b16": VerifyConfig(
+        name="p70b_k15_b16", n_layers=80, d=8192, n_q_heads=64, n_kv_heads=8, head_dim=128,
+        ffn=28672, vocab=128256, dtype="bf16", batch=16, K=15, kv_len=1024, p_match=0.7,
+        temperatures=(0.3, 1.0, 3.0)),
+    "p405b_k25_slice": VerifyConfig(
+        name="p405b_k25_slice", n_layers=8, d=16384, n_q_heads=128, n_kv_heads=8,
+        head_dim=128, ffn=53248, vocab=128256, dtype="bf16", batch=1, K=25,
+        kv_len=1024, p_match=0.75, temperatures=(1.0,)),
 }
 
 # Tensor identifiers: one integer per logical tensor; layer tensors add

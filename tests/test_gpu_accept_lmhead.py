@@ -130,7 +130,7 @@ def test_lmhead_bf16_many_rows(fb, M, d, V):
     prefetch ring is deep."""
     got, ref = lmhead_case(fb, M, d, V, "bf16", hidden_std=4.0)
     check_lmhead(got, ref, 2e-3)
-    for wm in (2, 3, 6):
+    for wm in (2, 3, 4, 6):
         fb.fly_set_tuning("gemm_tiled", wm)
         try:
             got, ref = lmhead_case(fb, M, d, V, "bf16", hidden_std=4.0, seed=3)

@@ -84,6 +84,13 @@ def test_c4_one_layer_full_width():
     one_layer_case(C4)
 
 
+@pytest.mark.parametrize("name", ["p70b_k15", "p70b_k15_b16", "p405b_k25_slice"])
+def test_paper_sized_blocks_one_layer_full_width(name):
+    # K = 15 / 25 at batch 1 (16 / 26 rows; 128 / 416 query rows per KV head) and K = 15 at
+    # batch 16 (256 rows: the LDS-tiled GEMMs)
+    one_layer_case(synth.CONFIGS[name])
+
+
 def lmhead_full(cfg, M, sample_rows=None):
     from paper_2511_22972_amd import binding as fb
     d, V = cfg.d, cfg.vocab

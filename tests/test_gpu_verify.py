@@ -246,7 +246,7 @@ def test_gateup_swiglu_stage_bf16_many_rows():
     """The same stage above 128 rows, where the LDS-tiled GEMM takes over."""
     from paper_2511_22972_amd import binding as fb
     cases = [(M, d, F, 0) for M, d, F in ((200, 128, 16 * 37), (389, 256, 1056), (145, 32, 16), (1088, 64, 512))]
-    cases += [(389, 256, 1056, shape) for shape in (2, 3, 6)]
+    cases += [(389, 256, 1056, shape) for shape in (2, 3, 4, 6)]
     for M, d, F, shape in cases:
         fb.fly_set_tuning("gemm_tiled", shape)
         x = synth.hash_normal(6, 320, (M, d), 1.0, torch.bfloat16, "cuda")
@@ -274,7 +274,7 @@ def test_projection_partials_bf16():
     from paper_2511_22972_amd import binding as fb
     cases = [(M, Kd, N, 0) for M, Kd, N in ((36, 1024, 272), (100, 4096, 512), (200, 2048, 528),
                                             (389, 512, 1040), (1088, 1024, 256), (145, 32, 16))]
-    cases += [(389, 2048, 528, shape) for shape in (2, 3, 6)]
+    cases += [(389, 2048, 528, shape) for shape in (2, 3, 4, 6)]
     for M, Kd, N, shape in cases:
         fb.fly_set_tuning("gemm_tiled", shape)
         x = synth.hash_normal(7, 330, (M, Kd), 1.0, torch.bfloat16, "cuda")
