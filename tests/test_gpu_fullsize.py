@@ -2,7 +2,8 @@
 configuration bench.py times (same shapes, hence the same kernel plans).
 
 The oracle cannot run a whole 80-layer step in test time, and free-running
-bf16 agreement at depth is not pinned anyway (numerics).  So:
+bf16 agreement at depth is not pinned anyway (rounding flips decorrelate the two
+sides at full width).  So:
   * every stage is compared with the oracle at full width on seeded stage
     inputs (one decoder layer from a seeded residual stream; the LM head from
     seeded hidden states, all rows or a sample of rows);
