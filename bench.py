@@ -179,7 +179,32 @@ def roofline_only(cfg, args):
     desc = fb.make_desc(cfg)
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     es = 2 if cfg.dtype == "bf16" else 4
-    if cfg.dtype == "bf16" and cfg.M > 128:
+    if args.kernel == "attention":
+        # the KV-streaming phase alone: split-KV attention + merge of the splits, one layer's cache
+        cap = (cfg.kv_len + cfg.K + 1 + 63) // 64 * 64
+        one = cfg.replace(n_layers=1)
+        desc1 = fb.make_desc(one)
+        kv = fb.KVCache(desc1, cfg.batch, cap)
+        k, v = synth.make_kv_prefix(one, 0, "cuda")
+        kv.load_prefix(0, k, v)
+        del k, v
+        kv.set_lengths([cfg.kv_len] * cfg.batch)
+        q = synth.hash_normal(cfg.seed, 960, (cfg.M, cfg.q_dim), 1.0, tdt, "cuda")
+        o = torch.empty_like(q)
+        ws = fb.alloc_workspace(fb.fly_workspace_bytes(desc1, cfg.batch, cfg.K, cfg.kv_len))
+
+        def attention():
+            fb.fly_attention(desc1, kv, 0, q, o, cfg.batch, cfg.K, ws)
+
+        ms = time_region(attention, args.steps, args.warmup)
+        nbytes = 2 * cfg.batch * (cfg.kv_len + cfg.K + 1) * cfg.kv_dim * es
+        flops = 4.0 * cfg.batch * cfg.n_q_heads * (cfg.K + 1) * (cfg.kv_len + cfg.K + 1) * cfg.head_dim
+        print(json.dumps({"kernel": "attention (split-KV kernel + merge)", "workload": cfg.name,
+                          "launches": args.steps + args.warmup, "avg_launch_us": ms * 1e3,
+                          "bytes_per_launch": nbytes, "achieved_GBps": nbytes / (ms * 1e-3) / 1e9,
+                          "flops_per_launch": flops, "achieved_TFLOPs": flops / (ms * 1e-3) / 1e12}))
+        return
+    if args.kernel == "lmhead" or (args.kernel == "auto" and cfg.dtype == "bf16" and cfg.M > 128):
         # contraction regime: the dominant kernel is the LM head with fused row statistics
         w_lm = torch.empty(cfg.d * cfg.vocab, dtype=tdt, device="cuda")
         fb.fly_pack_weight(synth.make_weight(cfg, "w_lm", -1, "cuda"), w_lm, cfg.vocab)
@@ -234,6 +259,8 @@ def main():
     ap.add_argument("--workload", default="c3_70b", choices=sorted(synth.CONFIGS))
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel", default="auto", choices=["auto", "gateup", "lmhead", "attention"],
+                    help="with --roofline-only: which kernel to launch alone (auto = the dominant one)")
     ap.add_argument("--roofline-only", action="store_true",
                     help="run only the dominant kernel (gate/up GEMM, isolated launches) and a 1 GiB "
                          "device copy of known size; for hardware-counter passes (use with --layers)")
