@@ -264,6 +264,8 @@ def main():
     ap.add_argument("--roofline-only", action="store_true",
                     help="run only the dominant kernel (gate/up GEMM, isolated launches) and a 1 GiB "
                          "device copy of known size; for hardware-counter passes (use with --layers)")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="library tuning knob (fly_set_tuning), e.g. fuse=1; for experiments")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)",
@@ -273,6 +275,10 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    for kv_pair in args.tune:
+        from paper_2511_22972_amd import binding as _fb
+        key, _, val = kv_pair.partition("=")
+        _fb.fly_set_tuning(key, int(val))
     cfg = synth.CONFIGS[args.workload]
     if args.layers:
         cfg = cfg.replace(n_layers=args.layers)
