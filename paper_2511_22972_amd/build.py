@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfly.so")
-SOURCES = ["fly_api.hip", "fly_gemm.hip", "fly_gemm_tiled.hip", "fly_misc.hip", "fly_attn.hip", "fly_decode.hip"]
+SOURCES = ["fly_api.hip", "fly_gemm.hip", "fly_gemm_tiled.hip", "fly_gemm_wide.hip", "fly_misc.hip", "fly_attn.hip", "fly_decode.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wno-unused-value",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -39,7 +39,7 @@ def build(verbose: bool = False) -> str:
             print(err, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=7) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB],
                        capture_output=True, text=True)

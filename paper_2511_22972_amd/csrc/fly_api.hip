@@ -14,6 +14,7 @@ int g_force_splits = 0;
 int g_target_wgs = 256;
 int g_mt_max = 9;
 int g_tiled = 0;  // 0 automatic, 1 never, 2, 3, 4 or 6: always, with that workgroup shape
+int g_wide = 0;   // 0 automatic (129..256 rows), 1 never, 5, 6 or 8: always, with that many 32-row tiles
 
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 
@@ -56,7 +57,7 @@ int splits_for(int nblocks, int nchunks) {
 // 256 or 384 rows: the shape that pads M least wins, the larger one on a tie (fewer
 // bytes staged per flop).
 GemmPlan plan_gemm_tiled(int M, int N, int Kd, bool allow_split, int forced) {
-  GemmPlan p{1, 1, 1, 1, 3};
+  GemmPlan p{1, 1, 1, 1, 3, 0};
   auto padded = [&](int shape) {
     const int rows = gemm_bf16_tiled_rows(shape);
     return (M + rows - 1) / rows * rows;
@@ -85,10 +86,36 @@ GemmPlan plan_gemm_tiled(int M, int N, int Kd, bool allow_split, int forced) {
   return p;
 }
 
+// 129..256 rows: the weight-streaming kernel with 32 x 32 tiles, one workgroup per
+// 256 columns.  Narrow outputs reach one workgroup per compute unit by split-K
+// with at least sixteen 64-wide chunks per split.
+GemmPlan plan_gemm_wide(int M, int N, int Kd, bool allow_split, int forced) {
+  GemmPlan p{1, 1, 1, 1, 0, 0};
+  p.wide = forced ? forced : M <= 160 ? 5 : M <= 192 ? 6 : 8;
+  if (allow_split) {
+    const int wgs = (N / 16 + 15) / 16;
+    const int nchunks = (Kd / 32 + 1) / 2;
+    int s = g_force_splits ? g_force_splits : (g_target_wgs + wgs / 2) / wgs;
+    int max_splits = nchunks / 16;
+    if (s > max_splits) s = max_splits;
+    if (s > 16) s = 16;
+    if (s < 1) s = 1;
+    const int cps = (nchunks + s - 1) / s;  // drop empty trailing splits
+    p.splits = (nchunks + cps - 1) / cps;
+  }
+  return p;
+}
+
 GemmPlan plan_gemm(int M, int N, int Kd, bool allow_split, bool need_even_nt) {
+  // Measured at the 405B-slice (136 rows) and 70B batch-16 (256 rows) shapes: up to 192 rows the
+  // wide kernel wins or ties for every GEMM; at 193..256 rows it wins for the GEMMs without
+  // split-K (gate/up, LM head) and the LDS-tiled kernel for the split-K projections.
+  if (g_wide >= 5 || (g_wide == 0 && g_tiled < 2 && M > 128 && (M <= 192 || (M <= 256 && !allow_split))))
+    return plan_gemm_wide(M, N, Kd, allow_split, g_wide >= 5 ? g_wide : 0);
   if (g_tiled >= 2 || (g_tiled == 0 && M > 128)) return plan_gemm_tiled(M, N, Kd, allow_split, g_tiled);
   GemmPlan p;
   p.tiled = 0;
+  p.wide = 0;
   const int rows_max = g_mt_max * 16;
   p.mblocks = (M + rows_max - 1) / rows_max;
   p.mt = p.mblocks > 1 ? g_mt_max : pick_mt(M);
@@ -386,7 +413,7 @@ const char* fly_strerror(fly_status s) {
   return "unknown status";
 }
 
-// Tuning knobs for experiments: "gemm_nt" (1, 2, 4; 0 = automatic), "gemm_tiled",
+// Tuning knobs for experiments: "gemm_nt" (1, 2, 4; 0 = automatic), "gemm_tiled", "gemm_wide",
 // "gemm_splits" (0 = automatic), "target_wgs" (workgroups a launch aims for).
 fly_status fly_set_tuning(const char* key, int32_t value) {
   if (!key) return FLY_ERR_NULL_POINTER;
@@ -408,6 +435,9 @@ fly_status fly_set_tuning(const char* key, int32_t value) {
   } else if (!strcmp(key, "gemm_tiled")) {
     if (value != 0 && value != 1 && gemm_bf16_tiled_rows(value) == 0) return FLY_ERR_BAD_SHAPE;
     g_tiled = value;
+  } else if (!strcmp(key, "gemm_wide")) {
+    if (value != 0 && value != 1 && value != 5 && value != 6 && value != 8) return FLY_ERR_BAD_SHAPE;
+    g_wide = value;
   } else if (!strcmp(key, "target_wgs")) {
     if (value < 1) return FLY_ERR_BAD_SHAPE;
     g_target_wgs = value;

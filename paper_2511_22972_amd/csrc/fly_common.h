@@ -84,6 +84,42 @@ __device__ __forceinline__ RowStat stat_shfl_xor(const RowStat& a, int o) {
   return r;
 }
 
+// LDS-direct load: every lane gives its own global address of 16 bytes, the wave's
+// 1 KiB lands at lds_base + 16 * lane (lds_base wave-uniform, passed in M0).  It
+// is issued from inline assembly on purpose: the compiler's automatic wait
+// insertion cannot tell the ring slots apart and would wait for ALL outstanding
+// loads before every LDS read; the waits for these loads are placed by hand
+// (FLY_WAIT_VMCNT).  Unknown to the compiler's counters, they can only make its
+// own vmcnt waits longer than needed, never shorter (loads complete in order).
+// (M0 is reserved by the compiler, which warns about the clobber; nothing else
+// in this file uses M0, and the clobber makes the compiler reload it if it did.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void global_to_lds16(const void* gptr, const void* lds_base) {
+  const uint32_t lds_addr =
+      (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) void*)lds_base;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :
+               : "s"(lds_addr), "v"(gptr)
+               : "memory", "m0");
+}
+#pragma clang diagnostic pop
+#define FLY_GLOBAL_TO_LDS16(gptr, lptr) global_to_lds16((const void*)(gptr), (const void*)(lptr))
+
+// s_waitcnt vmcnt(n) only (expcnt and lgkmcnt left at "no wait").
+#define FLY_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+#define FLY_WAIT_LGKMCNT0() __builtin_amdgcn_s_waitcnt(0xC07F)
+// Workgroup barrier without the fence of __syncthreads (that fence would wait
+// for ALL outstanding LDS-direct loads, also those of the stages still being
+// prefetched).  The waits are placed by hand; the empty asm statements and the
+// scheduling barriers keep the compiler from moving LDS accesses across it.
+#define FLY_BARE_BARRIER()              \
+  asm volatile("" ::: "memory");        \
+  __builtin_amdgcn_sched_barrier(0);    \
+  __builtin_amdgcn_s_barrier();         \
+  __builtin_amdgcn_sched_barrier(0);    \
+  asm volatile("" ::: "memory")
+
 // ---- host-side launchers (defined in the kernel sources) -------------------
 struct GemmPlan {
   int mt;      // 16-row tiles of activations held per workgroup (1,2,3,5,9)
@@ -92,6 +128,8 @@ struct GemmPlan {
   int mblocks; // row blocks (activations beyond 144 rows re-stream the weights)
   int tiled;   // 0: weight-streaming kernel (mt, nt as above); else the LDS-tiled kernel with
                // workgroups of 256 columns x 128 (2), 192 (3), 256 (4) or 384 (6) rows (mt, nt unused)
+  int wide;    // 0, or the weight-streaming kernel for 129..256 rows with this many 32-row tiles
+               // (5, 6, 8); takes precedence over the other fields except splits
 };
 
 enum GemmEpilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_LMHEAD = 2 };
@@ -112,6 +150,10 @@ int gemm_bf16_lmhead_parts(int N, const GemmPlan& plan);
 hipError_t launch_gemm_bf16_tiled(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale,
                                   int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st);
 int gemm_bf16_tiled_lmhead_parts(int N, int tiled);
+// Weight-streaming variant for 129..256 rows (called through launch_gemm_bf16 when plan.wide != 0).
+hipError_t launch_gemm_bf16_wide(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale, int M,
+                                 int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st);
+int gemm_bf16_wide_lmhead_parts(int N);
 int gemm_bf16_tiled_rows(int tiled);
 int gemm_bf16_tiled_cols(int tiled);
 

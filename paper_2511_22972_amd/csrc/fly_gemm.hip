@@ -394,6 +394,7 @@ static hipError_t launch_gemm_mt(const bf16_t* X, const bf16_t* Wp, void* out,
 
 hipError_t launch_gemm_bf16(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale,
                             int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st) {
+  if (plan.wide) return launch_gemm_bf16_wide(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
   if (plan.tiled) return launch_gemm_bf16_tiled(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
   // Host-side shape checks: the kernel assumes whole 16-column tiles and whole
   // 32-row k-steps, and that the row blocks cover M.
@@ -412,6 +413,7 @@ hipError_t launch_gemm_bf16(const bf16_t* X, const bf16_t* Wp, void* out, const 
 }
 
 int gemm_bf16_lmhead_parts(int N, const GemmPlan& plan) {
+  if (plan.wide) return gemm_bf16_wide_lmhead_parts(N);
   if (plan.tiled) return gemm_bf16_tiled_lmhead_parts(N, plan.tiled);
   int ntiles = N / 16;
   int nblocks = (ntiles + 4 * plan.nt - 1) / (4 * plan.nt);

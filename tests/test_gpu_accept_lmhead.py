@@ -139,6 +139,21 @@ def test_lmhead_bf16_many_rows(fb, M, d, V):
         check_lmhead(got, ref, 2e-3)
 
 
+@pytest.mark.parametrize("M,d,V,tiles", [(129, 256, 2048 + 48, 0), (160, 96, 16 * 131, 5), (161, 544, 1040, 6),
+                                         (192, 32, 16, 6), (200, 320, 4096 + 16, 0), (256, 64, 272, 8),
+                                         (97, 160, 528, 5), (140, 128, 256, 8)])
+def test_lmhead_bf16_wide_rows(fb, M, d, V, tiles):
+    """129..256 rows take the weight-streaming kernel with 32 x 32 tiles (5, 6 or 8 row tiles per
+    wave): ragged last tile, a vocabulary that is not a multiple of the 256-column block, an odd
+    number of k-tiles, fewer chunks than the register ring is deep."""
+    fb.fly_set_tuning("gemm_wide", tiles)
+    try:
+        got, ref = lmhead_case(fb, M, d, V, "bf16", hidden_std=4.0, seed=5)
+    finally:
+        fb.fly_set_tuning("gemm_wide", 0)
+    check_lmhead(got, ref, 2e-3)
+
+
 def test_lmhead_planted_argmax_and_ties(fb):
     V, d, M = 8192, 64, 8
     cols = [0, 15, 16, 255, 256, 4095, 8190, 8191]

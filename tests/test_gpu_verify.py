@@ -247,6 +247,7 @@ def test_gateup_swiglu_stage_bf16_many_rows():
     from paper_2511_22972_amd import binding as fb
     cases = [(M, d, F, 0) for M, d, F in ((200, 128, 16 * 37), (389, 256, 1056), (145, 32, 16), (1088, 64, 512))]
     cases += [(389, 256, 1056, shape) for shape in (2, 3, 4, 6)]
+    cases += [(M, 256, 1056, shape) for M in (145, 200) for shape in (2, 3)]  # also where "wide" is the default
     for M, d, F, shape in cases:
         fb.fly_set_tuning("gemm_tiled", shape)
         x = synth.hash_normal(6, 320, (M, d), 1.0, torch.bfloat16, "cuda")
@@ -266,6 +267,63 @@ def test_gateup_swiglu_stage_bf16_many_rows():
         diff = (a.float().cpu().double() - ref).abs()
         assert torch.all(diff <= ref.abs() * 2.0 ** -7 + 1e-7), (M, d, F, shape, diff.max())
         assert (diff == 0).double().mean().item() > 0.99
+
+
+@pytest.mark.gpu
+def test_gateup_swiglu_stage_bf16_wide_rows():
+    """The same stage at 129..256 rows (weight-streaming kernel with 32 x 32 tiles), every
+    row-tile count, ragged rows / columns / k-tiles."""
+    from paper_2511_22972_amd import binding as fb
+    cases = [(129, 256, 1056, 0), (160, 96, 16 * 37, 5), (161, 544, 512, 6), (192, 32, 16, 6),
+             (200, 320, 2048 + 16, 0), (256, 64, 144, 8), (100, 160, 272, 5), (150, 1024, 256, 8)]
+    for M, d, F, tiles in cases:
+        fb.fly_set_tuning("gemm_wide", tiles)
+        x = synth.hash_normal(8, 320, (M, d), 1.0, torch.bfloat16, "cuda")
+        wg = synth.hash_normal(8, 321, (d, F), 0.05, torch.bfloat16, "cuda")
+        wu = synth.hash_normal(8, 322, (d, F), 0.05, torch.bfloat16, "cuda")
+        wp = torch.empty(d * 2 * F, dtype=torch.bfloat16, device="cuda")
+        fb.fly_pack_weight(wg, wp, 2 * F, 0, 2)
+        fb.fly_pack_weight(wu, wp, 2 * F, 1, 2)
+        a = torch.zeros(M, F, dtype=torch.bfloat16, device="cuda")
+        try:
+            fb.fly_gateup_swiglu(x, wp, a)
+        finally:
+            fb.fly_set_tuning("gemm_wide", 0)
+        torch.cuda.synchronize()
+        xd = x.float().cpu().double()
+        ref = O.round_to_bf16(O.silu(xd @ wg.float().cpu().double()) * (xd @ wu.float().cpu().double()))
+        diff = (a.float().cpu().double() - ref).abs()
+        assert torch.all(diff <= ref.abs() * 2.0 ** -7 + 1e-7), (M, d, F, tiles, diff.max())
+        assert (diff == 0).double().mean().item() > 0.99
+
+
+@pytest.mark.gpu
+def test_projection_partials_bf16_wide_rows():
+    """Split-K projection at 129..256 rows: the partial sums add up to x W (ragged last split,
+    more splits asked for than there are chunks)."""
+    from paper_2511_22972_amd import binding as fb
+    cases = [(136, 4096, 512, 0, 0), (200, 2048, 528, 0, 0), (256, 1056, 1040, 8, 0), (160, 2080, 256, 5, 5),
+             (192, 96, 16, 6, 0), (129, 3072, 272, 0, 7), (150, 1024, 256, 6, 16)]
+    for M, Kd, N, tiles, force_splits in cases:
+        fb.fly_set_tuning("gemm_wide", tiles)
+        fb.fly_set_tuning("gemm_splits", force_splits)
+        x = synth.hash_normal(9, 330, (M, Kd), 1.0, torch.bfloat16, "cuda")
+        w = synth.hash_normal(9, 331, (Kd, N), 0.05, torch.bfloat16, "cuda")
+        wp = torch.empty(Kd * N, dtype=torch.bfloat16, device="cuda")
+        fb.fly_pack_weight(w, wp, N)
+        partial = torch.full((16 * M * N,), float("nan"), dtype=torch.float32, device="cuda")
+        try:
+            splits = fb.fly_proj_partial(x, wp, partial, N)
+        finally:
+            fb.fly_set_tuning("gemm_wide", 0)
+            fb.fly_set_tuning("gemm_splits", 0)
+        torch.cuda.synchronize()
+        assert 1 <= splits <= 16
+        got = partial[: splits * M * N].view(splits, M, N).double().sum(0).cpu()
+        ref = x.float().cpu().double() @ w.float().cpu().double()
+        scale = ref.abs().max().item()
+        assert torch.isfinite(got).all()
+        assert (got - ref).abs().max().item() <= 2e-5 * scale + 1e-6, (M, Kd, N, tiles, splits)
 
 
 @pytest.mark.gpu
