@@ -187,15 +187,28 @@ def test_causality_on_device():
     assert not np.array_equal(a["lse"][:, 3:], b["lse"][:, 3:])
 
 
-def test_attention_stage_bf16():
+ATTENTION_STAGE_CASES = [
+    # (query heads, KV heads, K, query tiles per workgroup; 0 = automatic) -> rows per KV head
+    (16, 2, 8, 0),    # 72 rows, 3 tiles: a wave owns (tile, half of a stage's keys)
+    (8, 2, 8, 0),     # 36 rows, 2 tiles
+    (16, 2, 16, 0),   # 136 rows, 5 tiles: a wave owns a whole tile
+    (16, 2, 24, 0),   # 200 rows, 7 tiles
+    (32, 2, 19, 0),   # 320 rows: two query blocks of 5 tiles that stream the same keys
+    (16, 2, 16, 2),   # 136 rows as three query blocks of 2, 2 and 1 tiles
+    (16, 2, 30, 0),   # 248 rows, 8 tiles, the longest block one workgroup holds
+]
+
+
+@pytest.mark.parametrize("hq,hkv,K,block_tiles", ATTENTION_STAGE_CASES)
+def test_attention_stage_bf16(hq, hkv, K, block_tiles):
     """fly_attention alone on seeded q and cache: one rounding (the bf16 output)
     separates the two sides, so elements agree to one bf16 ulp and almost all
-    are identical.  Covers ragged lengths, a cache that ends mid-tile, and 72
-    query rows per KV head over several cache splits."""
+    are identical.  Covers ragged lengths, a cache that ends mid-tile, several
+    cache splits, and every way the query tiles are dealt to waves and workgroups."""
     from paper_2511_22972_amd import binding as fb
-    cfg = synth.CONFIGS["c3_70b"].replace(n_layers=1, n_q_heads=16, n_kv_heads=2, batch=3, K=8,
+    cfg = synth.CONFIGS["c3_70b"].replace(n_layers=1, n_q_heads=hq, n_kv_heads=hkv, batch=3, K=K,
                                           kv_len=1000)
-    kv_lens = [1000, 517, 3]
+    kv_lens = [1000 - K, 517, 3]
     R = cfg.K + 1
     desc = fb.make_desc(cfg)
     kv = fb.KVCache(desc, cfg.batch, 1024)
@@ -204,8 +217,12 @@ def test_attention_stage_bf16():
     kv.set_lengths(kv_lens)
     q = synth.hash_normal(cfg.seed, 310, (cfg.M, cfg.q_dim), 2.0, torch.bfloat16, "cuda")
     o = torch.zeros_like(q)
-    ws = fb.alloc_workspace(fb.fly_workspace_bytes(desc, cfg.batch, cfg.K, max(kv_lens)))
-    fb.fly_attention(desc, kv, 0, q, o, cfg.batch, cfg.K, ws)
+    fb.fly_set_tuning("attn_block_tiles", block_tiles)
+    try:
+        ws = fb.alloc_workspace(fb.fly_workspace_bytes(desc, cfg.batch, cfg.K, max(kv_lens)))
+        fb.fly_attention(desc, kv, 0, q, o, cfg.batch, cfg.K, ws)
+    finally:
+        fb.fly_set_tuning("attn_block_tiles", 0)
     torch.cuda.synchronize()
     got = o.float().cpu().double().view(cfg.batch, R, cfg.n_q_heads, cfg.head_dim)
     num = O.Numerics("bf16")
