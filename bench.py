@@ -204,7 +204,7 @@ def roofline_only(cfg, args):
                           "bytes_per_launch": nbytes, "achieved_GBps": nbytes / (ms * 1e-3) / 1e9,
                           "flops_per_launch": flops, "achieved_TFLOPs": flops / (ms * 1e-3) / 1e12}))
         return
-    if args.kernel == "lmhead" or (args.kernel == "auto" and cfg.dtype == "bf16" and cfg.M > 128):
+    if args.kernel == "lmhead" or (args.kernel == "auto" and cfg.dtype == "bf16" and cfg.M > 256):
         # contraction regime: the dominant kernel is the LM head with fused row statistics
         w_lm = torch.empty(cfg.d * cfg.vocab, dtype=tdt, device="cuda")
         fb.fly_pack_weight(synth.make_weight(cfg, "w_lm", -1, "cuda"), w_lm, cfg.vocab)
@@ -342,17 +342,21 @@ def main():
                "achieved_TFLOPs": lm_flops / (lm_ms * 1e-3) / 1e12, "achieved_GBps": lm_bytes / (lm_ms * 1e-3) / 1e9,
                "frac_of_mfma_peak": lm_flops / (lm_ms * 1e-3) / 1e12 / mfma_peak,
                "frac_of_hbm_peak": lm_bytes / (lm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
-    # Above 128 rows the GEMMs are dense contractions (LDS-tiled kernel): the
-    # dominant kernel is then the LM head and the bound is the matrix cores.
-    contraction = cfg.dtype == "bf16" and cfg.M > 128
+    # Up to 256 rows every GEMM is bound by streaming its weights (the weight-
+    # streaming kernels; 256 flop per weight byte is still below the ridge) and the
+    # dominant kernel is gate/up.  Beyond that the GEMMs are dense contractions
+    # (LDS-tiled kernel): the dominant kernel is then the LM head and the bound is
+    # the matrix cores.
+    contraction = cfg.dtype == "bf16" and cfg.M > 256
     if contraction:
         roofline = {"kernel": "gemm_bf16_tiled_kernel (LM head + fused row statistics)", "bound": "mfma",
                     "achieved": lm_head["achieved_TFLOPs"], "peak": mfma_peak, "unit": "TFLOP/s",
                     "frac": lm_head["frac_of_mfma_peak"], "traffic": None,
                     "flops_per_launch": lm_flops, "avg_launch_us": lm_ms * 1e3}
     else:
-        roofline = {"kernel": "gemm_bf16_kernel (gate/up projection + SwiGLU)" if cfg.dtype == "bf16"
-                    else "gemm_f32_kernel (gate/up projection + SwiGLU)",
+        gu_kernel = ("gemm_f32_kernel" if cfg.dtype != "bf16" else
+                     "gemm_bf16_kernel" if cfg.M <= 128 else "gemm_bf16_wide_kernel")
+        roofline = {"kernel": gu_kernel + " (gate/up projection + SwiGLU)",
                     "bound": "hbm", "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": gu_gbs / HBM_PEAK_GBS,
                     "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if not args.layers else None,
