@@ -135,6 +135,25 @@ def time_region(fn, steps, warmup):
     return start.elapsed_time(end) / steps  # ms per call
 
 
+def graph_replay_ms(step, steps, warmup):
+    """The step captured in a HIP graph (it enqueues kernels only) and replayed:
+    ms per replay, or None where the runtime refuses the capture."""
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        return time_region(graph.replay, steps, warmup)
+    except Exception as e:  # reported, never fatal: the eager number is the headline
+        log(f"[bench] graph capture unavailable: {e}")
+        return None
+
+
 def cpu_baseline(cfg, tokens_np, layers_sampled=1):
     """The oracle timed on this host on a bounded sample: `layers_sampled`
     decoder layers plus the LM head, row statistics and acceptance rule for the
@@ -296,6 +315,7 @@ def main():
         fb.fly_verify_block(model, kv, tokens, row_scale, cfg.theta, cfg.window, out, ws)
 
     ms = time_region(step, args.steps, args.warmup)
+    graph_ms = graph_replay_ms(step, args.steps, args.warmup)
     accept_len = out.accept_len.cpu().numpy()
     s_total = int((accept_len + 1).sum())          # the paper's count: kept drafts + 1
     tokens_per_s = s_total / (ms * 1e-3)
@@ -377,6 +397,8 @@ def main():
         "gate_up": {"avg_launch_us": gu_ms * 1e3, "achieved_GBps": gu_gbs, "achieved_TFLOPs": gu_flops / (gu_ms * 1e-3) / 1e12},
         "lm_head": lm_head,
         "decode_loop": decode_loop_line(fb, cfg, desc, model, kv, row_scale),
+        "graph_replay": {"ms_per_step": graph_ms,
+                         "note": "the same step captured once in a HIP graph and replayed; equal to the eager time when the device, not the host launch path, is the limit"},
     }
     if not args.no_cpu_baseline:
         torch.cuda.synchronize()

@@ -368,3 +368,39 @@ def test_projection_partials_bf16():
         scale = ref.abs().max().item()
         assert torch.isfinite(got).all()
         assert (got - ref).abs().max().item() <= 2e-5 * scale + 1e-6, (M, Kd, N, shape, splits)
+
+
+def test_verify_block_replays_from_a_captured_graph():
+    """The step enqueues kernels and device copies only (no allocation, no
+    synchronisation), so a caller may capture it in a HIP graph.  Every replay,
+    with eager work of the program between the replays, gives bit for bit the
+    eager result."""
+    from paper_2511_22972_amd import binding as fb
+    for cfg in (B16_WIDE, C1.replace(batch=2, logit_gain=12.0, window=2)):
+        wl = GpuWorkload(cfg)
+        tokens = synth.hash_tokens(cfg.seed, 970, cfg.batch * (cfg.K + 1), cfg.vocab, "cuda").view(
+            cfg.batch, cfg.K + 1).to(torch.int32)
+        rs = helpers.row_scale(cfg).cuda()
+        eager = wl.verify(tokens.cpu().numpy(), rs)
+        out = fb.VerifyOutputs(cfg.batch, cfg.K, cfg.d, want_hidden=True)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):    # warm-up on the capture stream, as graph capture asks for
+            fb.fly_verify_block(wl.model, wl.kv, tokens, rs, cfg.theta, cfg.window, out, wl.ws)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            fb.fly_verify_block(wl.model, wl.kv, tokens, rs, cfg.theta, cfg.window, out, wl.ws)
+        for rep in range(3):
+            for name in ("accept_len", "next_token", "kv_len_out", "n_loose", "argmax"):
+                getattr(out, name).fill_(-7)
+            for name in ("h_norm", "p_top1", "lse", "hidden"):
+                getattr(out, name).fill_(float("nan"))
+            wl.ws.fill_(0x5A)                      # the workspace carries nothing between calls
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            for name in ("accept_len", "next_token", "kv_len_out", "n_loose", "argmax", "h_norm", "p_top1", "lse"):
+                assert np.array_equal(getattr(out, name).cpu().numpy(), eager[name]), (cfg.name, rep, name)
+            assert np.array_equal(out.hidden.cpu().numpy(), eager["hidden"]), (cfg.name, rep)
