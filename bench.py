@@ -34,6 +34,11 @@ F32_PEAK_TFLOPS = 157.3     # fp32 vector / matrix, published
 # HBM bytes per launch of the dominant kernel from hardware counters (FETCH_SIZE and
 # WRITE_SIZE passes scaled by a 1 GiB copy; profiles/gateup_gemm_c3_70b_hbm_counters.md).
 MEASURED_TRAFFIC_BYTES = {"c3_70b": 946.6e6}
+# The paper's own figure where a preset is its setting (Table 3: Llama-3.1-70B target, K = 15,
+# batch 1, one MI355X).  Context only: its software stack, prefix length and precision are not
+# stated, so vs_baseline stays null.
+PAPER_CONTEXT = {"p70b_k15": {"paper_reference": {"verify_ms_per_round": 58.62, "hardware": "1x MI355X",
+                                                   "source": "Table 3 (target verification)"}}}
 
 
 def log(*a):
@@ -390,7 +395,7 @@ def main():
         "config": {"workload": cfg.name, "n_layers": cfg.n_layers, "d": cfg.d, "heads": f"{cfg.n_q_heads}q/{cfg.n_kv_heads}kv",
                    "ffn": cfg.ffn, "vocab": cfg.vocab, "batch": cfg.batch, "K": cfg.K,
                    "kv_len": cfg.kv_len, "theta": cfg.theta, "W": cfg.window, "rows": cfg.M,
-                   "accepted_tokens_per_step": s_total},
+                   "accepted_tokens_per_step": s_total, **PAPER_CONTEXT.get(cfg.name, {})},
         "step_hbm": {"algorithmic_bytes": ab["total"], "achieved_GBps": ab["total"] / (ms * 1e-3) / 1e9,
                      "frac_of_peak": ab["total"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "roofline": roofline,
