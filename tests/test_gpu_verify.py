@@ -192,6 +192,8 @@ ATTENTION_STAGE_CASES = [
     (16, 2, 8, 0),    # 72 rows, 3 tiles: a wave owns (tile, half of a stage's keys)
     (8, 2, 8, 0),     # 36 rows, 2 tiles
     (16, 2, 16, 0),   # 136 rows, 5 tiles: a wave owns a whole tile
+    (16, 2, 20, 0),   # 168 rows, 6 tiles
+    (16, 2, 23, 0),   # 192 rows, 6 full tiles
     (16, 2, 24, 0),   # 200 rows, 7 tiles
     (32, 2, 19, 0),   # 320 rows: two query blocks of 5 tiles that stream the same keys
     (16, 2, 16, 2),   # 136 rows as three query blocks of 2, 2 and 1 tiles
