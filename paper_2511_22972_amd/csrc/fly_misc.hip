@@ -15,7 +15,19 @@ __global__ void embed_kernel(const int32_t* __restrict__ tokens, const WT* __res
   // token ids outside the vocabulary would read out of bounds: clamp
   tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
   const WT* e = embed + (int64_t)tok * d;
-  for (int i = threadIdx.x; i < d; i += blockDim.x) x[(int64_t)m * d + i] = Act<WT>::ld(e + i);
+  float* xr = x + (int64_t)m * d;
+  if constexpr (sizeof(WT) == 2) {
+    // rows are multiples of 32 elements and 16-byte aligned: eight bf16 per load
+    for (int i = threadIdx.x * 8; i < d; i += blockDim.x * 8) {
+      const u32x4 v = *(const u32x4*)(e + i);
+      *(f32x4*)(xr + i) = f32x4{__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xFFFF0000u),
+                                __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xFFFF0000u)};
+      *(f32x4*)(xr + i + 4) = f32x4{__uint_as_float(v.z << 16), __uint_as_float(v.z & 0xFFFF0000u),
+                                    __uint_as_float(v.w << 16), __uint_as_float(v.w & 0xFFFF0000u)};
+    }
+  } else {
+    for (int i = threadIdx.x; i < d; i += blockDim.x) xr[i] = Act<WT>::ld(e + i);
+  }
 }
 
 hipError_t launch_embed(const int32_t* tokens, const void* embed, int dtype, float* x, int M, int d,
