@@ -487,6 +487,7 @@ __global__ __launch_bounds__(64) void attention_f32_kernel(const float* __restri
     if (key < nvis) {
       const float* kr = kb + (int64_t)key * hd;
       float dot = 0.f;
+#pragma unroll 16
       for (int e = 0; e < hd; ++e) dot = fmaf(qs[e], kr[e], dot);
       s = dot * scale;
     }
@@ -497,6 +498,7 @@ __global__ __launch_bounds__(64) void attention_f32_kernel(const float* __restri
     acc0 *= corr;
     acc1 *= corr;
     int cnt = min(64, nvis - k0);
+#pragma unroll 8
     for (int jj = 0; jj < cnt; ++jj) {
       float pj = __shfl(p, jj, FLY_WAVE);
       if (lane < hd) acc0 = fmaf(pj, vb[(int64_t)lane * capacity + k0 + jj], acc0);

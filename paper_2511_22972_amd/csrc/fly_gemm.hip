@@ -421,17 +421,21 @@ int gemm_bf16_lmhead_parts(int N, const GemmPlan& plan) {
 }
 
 // ---------------------------------------------------------------------------
-// fp32 GEMM (tiny configuration): block = 64 columns x 4 k-slices, up to 8 rows.
+// fp32 GEMM (tiny configuration): block = 64 columns x 16 k-slices, up to 8 rows.
+// The shapes are a few hundred wide, so the kernel is bound by the latency of
+// its k loop: sixteen slices keep the loop short, the slices are added in
+// slice order (the result does not depend on scheduling).
 // ---------------------------------------------------------------------------
 #define F32_MB 8
+#define F32_KSL 16
 
 template <int EPI>
-__global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ X,
-                                                       const float* __restrict__ W,
-                                                       void* __restrict__ out,
-                                                       const float* __restrict__ row_scale, int M,
-                                                       int N, int Kd) {
-  __shared__ float red[4][F32_MB][64];
+__global__ __launch_bounds__(64 * F32_KSL) void gemm_f32_kernel(const float* __restrict__ X,
+                                                                const float* __restrict__ W,
+                                                                void* __restrict__ out,
+                                                                const float* __restrict__ row_scale,
+                                                                int M, int N, int Kd) {
+  __shared__ float red[F32_KSL][F32_MB][64];
   const int c = threadIdx.x & 63, slice = threadIdx.x >> 6;
   const int n = blockIdx.x * 64 + c;
   const int m0 = blockIdx.y * F32_MB;
@@ -439,7 +443,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 #pragma unroll
   for (int r = 0; r < F32_MB; ++r) acc[r] = 0.f;
   if (n < N) {
-    for (int k = slice; k < Kd; k += 4) {
+    // unrolled so that several weight loads are in flight; the additions stay in k order
+#pragma unroll 4
+    for (int k = slice; k < Kd; k += F32_KSL) {
       float w = W[(int64_t)k * N + n];
 #pragma unroll
       for (int r = 0; r < F32_MB; ++r) {
@@ -452,61 +458,52 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 #pragma unroll
   for (int r = 0; r < F32_MB; ++r) red[slice][r][c] = acc[r];
   __syncthreads();
-  // thread (slice, c) finishes rows slice and slice+4 of column c
+  // thread (slice, c) with slice < 8 finishes row `slice` of column c: it alone
+  // reads and rewrites that row's entries
+  const int r = slice, m = m0 + r;
+  if (slice < F32_MB) {
+    float t = red[0][r][c];
 #pragma unroll
-  for (int rr = 0; rr < 2; ++rr) {
-    int r = slice + 4 * rr;
-    // rows slice and slice+4 of column c are read and rewritten by this thread only
-    red[0][r][c] = red[0][r][c] + red[1][r][c] + red[2][r][c] + red[3][r][c];
+    for (int s = 1; s < F32_KSL; ++s) t += red[s][r][c];
+    red[0][r][c] = t;
   }
   __syncthreads();
+  if (slice >= F32_MB) return;
   if constexpr (EPI == EPI_PARTIAL) {
     float* o = (float*)out;
-#pragma unroll
-    for (int rr = 0; rr < 2; ++rr) {
-      int r = slice + 4 * rr, m = m0 + r;
-      if (m < M && n < N) o[(int64_t)m * N + n] = red[0][r][c];
-    }
+    if (m < M && n < N) o[(int64_t)m * N + n] = red[0][r][c];
   } else if constexpr (EPI == EPI_SWIGLU) {
     // 16-column tiles alternate gate / up inside the 64-column block
     float* o = (float*)out;
     const int Nh = N / 2;
     if (c < 32) {  // pair 0 uses tiles (0,1), pair 1 tiles (2,3) of this block
       const int pair = c >> 4, e = c & 15;
-#pragma unroll
-      for (int rr = 0; rr < 2; ++rr) {
-        int r = slice + 4 * rr, m = m0 + r;
-        int ncol = blockIdx.x * 64 + pair * 32 + e;  // gate column in the packed matrix
-        if (m < M && ncol + 16 < N) {
-          float gt = red[0][r][pair * 32 + e], up = red[0][r][pair * 32 + 16 + e];
-          o[(int64_t)m * Nh + blockIdx.x * 32 + pair * 16 + e] = silu_f(gt) * up;
-        }
+      int ncol = blockIdx.x * 64 + pair * 32 + e;  // gate column in the packed matrix
+      if (m < M && ncol + 16 < N) {
+        float gt = red[0][r][pair * 32 + e], up = red[0][r][pair * 32 + 16 + e];
+        o[(int64_t)m * Nh + blockIdx.x * 32 + pair * 16 + e] = silu_f(gt) * up;
       }
     }
   } else {
     f32x4* o = (f32x4*)out;
     const int nparts = gridDim.x;
+    float sc = (row_scale != nullptr && m < M) ? row_scale[m] : 1.f;
+    RowStat st = stat_empty();
+    if (n < N) {
+      st.m = red[0][r][c] * sc;
+      st.s = 1.f;
+      st.t = 0.f;
+      st.idx = n;
+    }
 #pragma unroll
-    for (int rr = 0; rr < 2; ++rr) {
-      int r = slice + 4 * rr, m = m0 + r;
-      float sc = (row_scale != nullptr && m < M) ? row_scale[m] : 1.f;
-      RowStat st = stat_empty();
-      if (n < N) {
-        st.m = red[0][r][c] * sc;
-        st.s = 1.f;
-        st.t = 0.f;
-        st.idx = n;
-      }
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) st = stat_merge(st, stat_shfl_xor(st, off));
-      if (c == 0 && m < M) {
-        f32x4 w;
-        w.x = st.m;
-        w.y = st.s;
-        w.z = st.t;
-        w.w = __int_as_float(st.idx);
-        o[(int64_t)m * nparts + blockIdx.x] = w;
-      }
+    for (int off = 1; off < 64; off <<= 1) st = stat_merge(st, stat_shfl_xor(st, off));
+    if (c == 0 && m < M) {
+      f32x4 w;
+      w.x = st.m;
+      w.y = st.s;
+      w.z = st.t;
+      w.w = __int_as_float(st.idx);
+      o[(int64_t)m * nparts + blockIdx.x] = w;
     }
   }
 }
@@ -515,7 +512,7 @@ hipError_t launch_gemm_f32(const float* X, const float* W, void* out, const floa
                            int N, int Kd, int epi, hipStream_t st) {
   if (N % 16 != 0 || M < 1 || Kd < 1) return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU && N % 32 != 0) return hipErrorInvalidValue;
-  dim3 grid((N + 63) / 64, (M + F32_MB - 1) / F32_MB), block(256);
+  dim3 grid((N + 63) / 64, (M + F32_MB - 1) / F32_MB), block(64 * F32_KSL);
   if (epi == EPI_PARTIAL)
     hipLaunchKernelGGL((gemm_f32_kernel<EPI_PARTIAL>), grid, block, 0, st, X, W, out, row_scale, M, N, Kd);
   else if (epi == EPI_SWIGLU)
