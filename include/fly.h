@@ -127,8 +127,7 @@ const char* fly_strerror(fly_status s);
  *   "gemm_nt"      16-column weight tiles per wavefront: 1, 2, 4; 0 = automatic
  *   "gemm_splits"  split-K factor of the projections: 1..16; 0 = automatic
  *   "gemm_mt_max"  most 16-row activation tiles one workgroup holds: 5 or 9 (default 9)
- *   "gemm_tiled"   0 = the LDS-tiled GEMM where it is the fastest (automatic: above 256 rows, and for
- *                  the split-K projections from 193 rows), 1 = never,
+ *   "gemm_tiled"   0 = the LDS-tiled GEMM above 256 rows (automatic), 1 = never,
  *                  2, 3, 4 or 6 = always, with workgroups of 128, 192, 256 or 384 rows
  *   "gemm_wide"    0 = the weight-streaming GEMM with 32-row tiles for 129..256 rows (automatic),
  *                  1 = never, 5, 6 or 8 = always, with that many 32-row tiles (M must fit)

@@ -93,7 +93,8 @@ GemmPlan plan_gemm_wide(int M, int N, int Kd, bool allow_split, int forced) {
   GemmPlan p{1, 1, 1, 1, 0, 0};
   p.wide = forced ? forced : M <= 160 ? 5 : M <= 192 ? 6 : 8;
   if (allow_split) {
-    const int wgs = (N / 16 + 15) / 16;
+    const int cols = gemm_bf16_wide_cols();
+    const int wgs = (N + cols - 1) / cols;
     const int nchunks = (Kd / 32 + 1) / 2;
     int s = g_force_splits ? g_force_splits : (g_target_wgs + wgs / 2) / wgs;
     int max_splits = nchunks / 16;
@@ -107,10 +108,9 @@ GemmPlan plan_gemm_wide(int M, int N, int Kd, bool allow_split, int forced) {
 }
 
 GemmPlan plan_gemm(int M, int N, int Kd, bool allow_split, bool need_even_nt) {
-  // Measured at the 405B-slice (136 rows) and 70B batch-16 (256 rows) shapes: up to 192 rows the
-  // wide kernel wins or ties for every GEMM; at 193..256 rows it wins for the GEMMs without
-  // split-K (gate/up, LM head) and the LDS-tiled kernel for the split-K projections.
-  if (g_wide >= 5 || (g_wide == 0 && g_tiled < 2 && M > 128 && (M <= 192 || (M <= 256 && !allow_split))))
+  // Measured at the 405B-slice (136 rows) and 70B batch-16 (256 rows) shapes: from 129 to 256 rows
+  // the wide kernel wins or ties for every GEMM of the layer and for the LM head.
+  if (g_wide >= 5 || (g_wide == 0 && g_tiled < 2 && M > 128 && M <= 256))
     return plan_gemm_wide(M, N, Kd, allow_split, g_wide >= 5 ? g_wide : 0);
   if (g_tiled >= 2 || (g_tiled == 0 && M > 128)) return plan_gemm_tiled(M, N, Kd, allow_split, g_tiled);
   GemmPlan p;

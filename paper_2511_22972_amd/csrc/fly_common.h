@@ -154,6 +154,7 @@ int gemm_bf16_tiled_lmhead_parts(int N, int tiled);
 hipError_t launch_gemm_bf16_wide(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale, int M,
                                  int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st);
 int gemm_bf16_wide_lmhead_parts(int N);
+int gemm_bf16_wide_cols();  // columns one workgroup covers
 int gemm_bf16_tiled_rows(int tiled);
 int gemm_bf16_tiled_cols(int tiled);
 

@@ -5,16 +5,20 @@
 //
 // In this range a GEMM of the forward is still bound by reading its weights
 // once from HBM (256 flop per weight byte against ~310 at the ridge), but the
-// accumulators of that many rows no longer fit the 16-row tiles of the kernel
-// for small blocks, and staging the weights in LDS (the kernel for many rows)
-// leaves too few weight bytes in flight per compute unit to keep HBM busy.
-// Here every wave streams the packed weight tiles of its own 64 columns
-// straight from global memory into matrix-core operand registers, through a
-// ring of k-chunks that keeps 24-32 KiB per wave in flight, and only the small
-// activation block is staged in LDS and shared by the four waves.  The product
-// is out^T[n, m] = sum_k W[k, n] X[m, k] in 32 x 32 tiles of
-// v_mfma_f32_32x32x16_bf16 (weights = A operand, activations = B operand); a
-// wave holds 2 x MT of them (MT = 5, 6 or 8 tiles of 32 rows).
+// matrix work is no longer small beside it, the accumulators of that many rows
+// do not fit the 16-row tiles of the kernel for small blocks, and staging the
+// weights in LDS (the kernel for many rows) leaves too few weight bytes in
+// flight per compute unit to keep HBM busy.  Here a workgroup of eight waves
+// covers 256 columns: every wave streams the packed weight tiles of its own 32
+// columns straight from global memory into matrix-core operand registers,
+// through a ring of k-chunks, and holds MT accumulator tiles of
+// v_mfma_f32_32x32x16_bf16 (MT = 5, 6 or 8 tiles of 32 rows; weights = A
+// operand, activations = B operand, out^T[n, m] = sum_k W[k, n] X[m, k]).  Two
+// waves share a SIMD, so one multiplies while the other waits for its weights.
+// Only the small activation block goes through LDS, copied there by LDS-direct
+// loads two chunks ahead, which keeps it out of the registers and, unlike a
+// register copy that must be waited for before it can be written to LDS, leaves
+// the weight ring in flight.
 #include "fly_common.h"
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -22,6 +26,13 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 namespace {
 
 constexpr int WIDE_KC = 2;  // 32-wide k-tiles per chunk (pipeline step)
+#ifndef WIDE_NWV
+#define WIDE_NWV 8
+#endif
+#ifndef WIDE_CG
+#define WIDE_CG 1
+#endif
+#define WIDE_COLS (32 * WIDE_CG * WIDE_NWV)
 
 __device__ __forceinline__ float silu_w(float x) { return x / (1.f + __expf(-x)); }
 
@@ -58,21 +69,26 @@ __device__ __forceinline__ void wide_row_stat(RowStat& run, const f32x16& v, flo
 }  // namespace
 
 // Grid: (column blocks of 256, split-K factor).
-template <int MT, int EPI, int RING>
-__global__ __launch_bounds__(256) void gemm_bf16_wide_kernel(
+// NWV waves per workgroup, each owning CG groups of 32 columns: a workgroup covers
+// 32 CG NWV columns.
+template <int MT, int EPI, int RING, int NWV, int CG>
+__global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
     const bf16_t* __restrict__ X, const u32x4* __restrict__ Wp, void* __restrict__ out,
     const float* __restrict__ row_scale, int M, int N, int Kd, int chunks_per_split, int nblocks) {
   constexpr int KC = WIDE_KC;
+  constexpr int WGS = 2 * CG * NWV;  // 16-column strips per workgroup
   // Workgroups are dealt to the eight XCDs round-robin by linear id; consecutive
   // column blocks go to different XCDs.
   const int nblock = blockIdx.x;
   if (nblock >= nblocks) return;
 
-  // LDS: two stages of the activation block.  One k-tile (32 wide) of 16 rows is
+  // LDS: ring of NSTG activation blocks.  One k-tile (32 wide) of 16 rows is
   // 1 KiB: a row is four 16-byte pieces, piece c of row r at position
   // 4 r + (c ^ ((r >> 1) & 3)), so that the operand reads of eight consecutive
-  // rows fall into distinct banks.
-  __shared__ u32x4 xs[2][KC][2 * MT][64];
+  // rows fall into distinct banks.  Group 2 MT is a dummy target of surplus pieces.
+  constexpr int XD = 2;          // the activation block is requested XD chunks ahead
+  constexpr int NSTG = XD + 1;
+  __shared__ u32x4 xs[NSTG][KC][2 * MT + 1][64];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -84,135 +100,150 @@ __global__ __launch_bounds__(256) void gemm_bf16_wide_kernel(
   const int kt_end = min(chunk_end * KC, ktiles);
   const int kt_last = max(kt_end - 1, 0);
   const int nstrips = N / 16;
-  const int strip0 = nblock * 16 + wave * 4;  // this wave's four 16-column strips
+  const int strip0 = nblock * WGS + wave * (2 * CG);  // this wave's 16-column strips (two per column group)
 
   // Weight fragment (column group cg, k-tile kt, half kh) of the 32x32x16 A
   // operand: lane (l32, hi) holds W[32 kt + 16 kh + 8 hi + i][32 cg + l32],
   // i = 0..7, which in the packed layout is the 16-byte piece of lane
   // (l32 % 16) + 16 (hi + 2 kh) of the tile of strip 2 cg + l32 / 16.  Strips
   // past the last one (ragged last workgroup) are clamped: loaded and
-  // multiplied like the others, never stored.  k-tiles at or past kt_end are
-  // clamped to the last valid one; they meet zeroed activations.
-  const u32x4* wbase[2];
+  // multiplied like the others, never stored.  k-tiles at or past kt_end (ragged
+  // last chunk, surplus pipeline steps) are clamped to the last valid one and
+  // the fragment is replaced by zeros once loaded.
+  const u32x4* wbase[CG];
 #pragma unroll
-  for (int cg = 0; cg < 2; ++cg) {
+  for (int cg = 0; cg < CG; ++cg) {
     const int strip = min(strip0 + 2 * cg + (l32 >> 4), nstrips - 1);
     wbase[cg] = Wp + (int64_t)strip * ktiles * 64 + (lane & 15) + 16 * hi;
   }
-  auto load_w = [&](u32x4 (&a)[2][KC][2], int chunk) {
+  auto load_w = [&](u32x4 (&a)[CG][KC][2], int chunk) {
 #pragma unroll
     for (int kt = 0; kt < KC; ++kt) {
       const int k = min(chunk * KC + kt, kt_last);
 #pragma unroll
-      for (int cg = 0; cg < 2; ++cg)
+      for (int cg = 0; cg < CG; ++cg)
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh)
           a[cg][kt][kh] = __builtin_nontemporal_load(wbase[cg] + (int64_t)k * 64 + 32 * kh);
     }
   };
 
-  // Activation pieces this wave stages per chunk: piece f = wave + 4 i is k-tile
-  // f / (2 MT), row group f % (2 MT); lane 4 r + c' fetches row r of the group,
-  // 16-byte piece c' ^ ((r >> 1) & 3), and writes it to position 4 r + c'.  Rows
-  // past M are clamped to row M-1 (they feed output rows that are never
-  // stored); k-tiles at or past kt_end read a clamped, valid address and are
-  // replaced by zeros when written to LDS.
-  constexpr int NXF = KC * 2 * MT / 4;
-  static_assert(NXF * 4 == KC * 2 * MT, "activation pieces must divide evenly over the four waves");
-  u32x4 xf[NXF];
-  const bf16_t* xrow[NXF];
-  int xkt[NXF], xgrp[NXF];
+  // Activation pieces this wave copies per chunk, global memory straight into
+  // LDS: piece f = wave + NWV i is k-tile f / (2 MT), row group f % (2 MT); lane
+  // 4 r + c' fetches row r of the group, 16-byte piece c' ^ ((r >> 1) & 3), and
+  // the wave's 1 KiB lands in lane order.  Every wave issues NXL loads (the
+  // hand-counted waits below rely on it): surplus ones re-load the last piece
+  // into the dummy group.  Rows past M are clamped to row M-1 (they feed output
+  // rows that are never stored), k-tiles past the end to the last valid one
+  // (they meet zeroed weight fragments).
+  constexpr int NPIECE = KC * 2 * MT;
+  constexpr int NXL = (NPIECE + NWV - 1) / NWV;
+  constexpr int NWL = CG * KC * 2;  // weight loads per wave and chunk
+  const bf16_t* xrow[NXL];
+  int xkt[NXL], xgrp[NXL];
 #pragma unroll
-  for (int i = 0; i < NXF; ++i) {
-    const int f = wave + 4 * i;
-    xkt[i] = f / (2 * MT);
-    xgrp[i] = f % (2 * MT);
+  for (int i = 0; i < NXL; ++i) {
+    const int f = wave + NWV * i;
+    const int fc = min(f, NPIECE - 1);
+    xkt[i] = fc / (2 * MT);
+    xgrp[i] = f < NPIECE ? fc % (2 * MT) : 2 * MT;
     const int r = lane >> 2;
     const int piece = (lane & 3) ^ ((r >> 1) & 3);
-    const int row = min(xgrp[i] * 16 + r, M - 1);
+    const int row = min((fc % (2 * MT)) * 16 + r, M - 1);
     xrow[i] = X + (int64_t)row * Kd + piece * 8;
   }
-  auto load_x = [&](int chunk) {
+  auto issue_x = [&](int chunk, int stage) {
+    asm volatile("" : "+s"(stage));  // keep the LDS address a register value (a folded constant is no valid asm operand)
 #pragma unroll
-    for (int i = 0; i < NXF; ++i) {
+    for (int i = 0; i < NXL; ++i) {
       const int k = min(chunk * KC + xkt[i], kt_last);
-      xf[i] = *(const u32x4*)(xrow[i] + (int64_t)k * 32);
-    }
-  };
-  auto store_x = [&](int stage, int chunk) {
-#pragma unroll
-    for (int i = 0; i < NXF; ++i) {
-      u32x4 v = xf[i];
-      if (chunk * KC + xkt[i] >= kt_end) v = u32x4{0u, 0u, 0u, 0u};
-      xs[stage][xkt[i]][xgrp[i]][lane] = v;
+      FLY_GLOBAL_TO_LDS16(xrow[i] + (int64_t)k * 32, &xs[stage][xkt[i]][xgrp[i]][0]);
     }
   };
 
-  f32x16 acc[2][MT];
+  f32x16 acc[CG][MT];
 #pragma unroll
-  for (int cg = 0; cg < 2; ++cg)
+  for (int cg = 0; cg < CG; ++cg)
 #pragma unroll
     for (int t = 0; t < MT; ++t)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[cg][t][r] = 0.f;
 
   // One chunk: for each 16-wide half of each k-tile, the MT activation
-  // fragments (32 rows x 16 k each) come from LDS and meet the two weight
+  // fragments (32 rows x 16 k each) come from LDS and meet the weight
   // fragments of the wave.  The fragments of the next half are requested before
-  // the multiplies of the current one.  The scheduling barriers pin that order:
-  // left alone, the compiler moves each LDS read next to its first use (every
-  // pair of multiplies then waits for a full LDS round trip) and sinks the
-  // activation loads below the weight loads (writing them to LDS then waits for
-  // the whole weight ring).
-  auto read_b = [&](bf16x8 (&b)[MT], int stage, int kt, int kh) {
+  // the multiplies of the current one; the scheduling barriers pin that order
+  // (left alone, the compiler moves each LDS read next to its first use and
+  // every pair of multiplies waits for a full LDS round trip).
+  // They are fetched in groups of BT row tiles (eight tiles at a time would need
+  // 32 registers twice over); group g covers half h = g / NG, tiles (g % NG) BT ...
+  constexpr int BT = MT == 8 ? 4 : MT;
+  constexpr int NG = MT / BT;
+  static_assert(NG * BT == MT, "row tiles must divide into groups");
+  auto read_b = [&](bf16x8 (&b)[BT], int stage, int g) {
+    const int h = g / NG, t0 = (g % NG) * BT;
+    const int kt = h >> 1, kh = h & 1;
     const int r = l32 & 15;
     const int c = hi + 2 * kh;
 #pragma unroll
-    for (int t = 0; t < MT; ++t)
-      b[t] = __builtin_bit_cast(bf16x8, xs[stage][kt][2 * t + (l32 >> 4)][4 * r + (c ^ ((r >> 1) & 3))]);
+    for (int t = 0; t < BT; ++t)
+      b[t] = __builtin_bit_cast(bf16x8, xs[stage][kt][2 * (t0 + t) + (l32 >> 4)][4 * r + (c ^ ((r >> 1) & 3))]);
   };
-  auto compute = [&](const u32x4 (&a)[2][KC][2], int stage) {
-    bf16x8 b[2][MT];
-    read_b(b[0], stage, 0, 0);
+  auto compute = [&](const u32x4 (&a)[CG][KC][2], int chunk, int stage) {
+    bf16x8 b[2][BT];
+    read_b(b[0], stage, 0);
 #pragma unroll
-    for (int h = 0; h < 2 * KC; ++h) {
+    for (int g = 0; g < 2 * KC * NG; ++g) {
+      const int h = g / NG, t0 = (g % NG) * BT;
       const int kt = h >> 1, kh = h & 1;
-      if (h + 1 < 2 * KC) read_b(b[(h + 1) & 1], stage, (h + 1) >> 1, (h + 1) & 1);
+      if (g + 1 < 2 * KC * NG) read_b(b[(g + 1) & 1], stage, g + 1);
       __builtin_amdgcn_sched_barrier(0);
+      const bool live = chunk * KC + kt < kt_end;
 #pragma unroll
-      for (int t = 0; t < MT; ++t)
+      for (int cg = 0; cg < CG; ++cg) {
+        u32x4 w = a[cg][kt][kh];
+        if (!live) w = u32x4{0u, 0u, 0u, 0u};
+        const bf16x8 wv = __builtin_bit_cast(bf16x8, w);
 #pragma unroll
-        for (int cg = 0; cg < 2; ++cg)
-          acc[cg][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[cg][kt][kh]),
-                                                               b[h & 1][t], acc[cg][t], 0, 0, 0);
+        for (int t = 0; t < BT; ++t)
+          acc[cg][t0 + t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wv, b[g & 1][t], acc[cg][t0 + t], 0, 0, 0);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  // Software pipeline over k-chunks with a ring of RING weight buffers in
-  // registers: while chunk c is multiplied, the weights of chunks c+1 ..
-  // c+RING-1 are in flight.  The activation loads of chunk c+1 are issued before
-  // the weight loads of chunk c+RING-1, so that writing them to LDS at the end
-  // of the step waits only for them and the older weight loads (loads retire in
-  // order).  Steps have no conditionals inside; the tail guards whole steps.
-  u32x4 ring[RING][2][KC][2];
-  int stage = 0;
-  auto step = [&](const u32x4 (&cur)[2][KC][2], u32x4 (&refill)[2][KC][2], int chunk) {
-    load_x(chunk + 1);
+  // Software pipeline over k-chunks.  Weights: a ring of RING register buffers;
+  // while chunk c is multiplied, chunks c+1 .. c+RING-1 are in flight.
+  // Activations: chunk c+XD is requested in step c and must have landed, for
+  // every wave, when step c+1 begins; the loads of a wave complete in order,
+  // so waiting until at most NWL + (XD-1)(NXL+NWL) loads are outstanding (those
+  // issued after the activation loads of chunk c+1) is enough, and the weight
+  // ring stays in flight (activations fetched through registers would have to be
+  // waited for before they can be written to LDS, which drains the ring down to
+  // its youngest chunk at every step).  The compiler does not know of the
+  // LDS-direct loads; its own waits for the weight registers therefore count
+  // too few loads behind them and wait a little longer than needed, never
+  // shorter.  The barrier at the end of a step also says that every wave is
+  // done reading stage c % NSTG, which step c+1 refills.
+  u32x4 ring[RING][CG][KC][2];
+  auto step = [&](const u32x4 (&cur)[CG][KC][2], u32x4 (&refill)[CG][KC][2], int chunk) {
+    issue_x(chunk + XD, (chunk - chunk_begin + XD) % NSTG);
     __builtin_amdgcn_sched_barrier(0);
     load_w(refill, chunk + RING - 1);
     __builtin_amdgcn_sched_barrier(0);
-    compute(cur, stage);
-    store_x(stage ^ 1, chunk + 1);
-    __syncthreads();
-    stage ^= 1;
+    compute(cur, chunk, (chunk - chunk_begin) % NSTG);
+    FLY_WAIT_VMCNT(NWL + (XD - 1) * (NXL + NWL));
+    FLY_WAIT_LGKMCNT0();
+    FLY_BARE_BARRIER();
   };
   if (chunk_begin < chunk_end) {
-    load_x(chunk_begin);
+#pragma unroll
+    for (int j = 0; j < XD; ++j) issue_x(chunk_begin + j, j);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int r = 0; r < RING - 1; ++r) load_w(ring[r], chunk_begin + r);
-    store_x(0, chunk_begin);
-    __syncthreads();
+    FLY_WAIT_VMCNT((RING - 1) * NWL + (XD - 1) * NXL);  // the activations of the first chunk
+    FLY_BARE_BARRIER();
     int c = chunk_begin;
     while (c + RING <= chunk_end) {
 #pragma unroll
@@ -222,6 +253,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_wide_kernel(
 #pragma unroll
     for (int r = 0; r < RING - 1; ++r)
       if (c + r < chunk_end) step(ring[r], ring[(r + RING - 1) % RING], c + r);
+    FLY_WAIT_VMCNT(0);  // surplus (clamped) loads must have landed before the wave may end
   }
 
   // ---- epilogues.  Accumulator register r of tile (cg, t) in lane l is
@@ -234,7 +266,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_wide_kernel(
       const int m = t * 32 + l32;
       if (m >= M) continue;
 #pragma unroll
-      for (int cg = 0; cg < 2; ++cg) {
+      for (int cg = 0; cg < CG; ++cg) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int n = n0 + 32 * cg + 8 * q + 4 * hi;
@@ -255,7 +287,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_wide_kernel(
       const int m = t * 32 + l32;
       if (m >= M) continue;
 #pragma unroll
-      for (int cg = 0; cg < 2; ++cg) {
+      for (int cg = 0; cg < CG; ++cg) {
         if (n0 + 32 * cg + 31 >= N) continue;
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
@@ -270,17 +302,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_wide_kernel(
         }
       }
     }
-  } else {  // EPI_LMHEAD: softmax statistics of this wave's 64 columns per row
+  } else {  // EPI_LMHEAD: softmax statistics of this wave's 32 CG columns per row
     f32x4* o = (f32x4*)out;
-    const int nparts = nblocks * 4;
-    const int part = nblock * 4 + wave;
+    const int nparts = nblocks * NWV;
+    const int part = nblock * NWV + wave;
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
       const int m = t * 32 + l32;
       const float sc = (row_scale != nullptr && m < M) ? row_scale[m] : 1.f;
       RowStat st = stat_empty();
 #pragma unroll
-      for (int cg = 0; cg < 2; ++cg) wide_row_stat(st, acc[cg][t], sc, n0 + 32 * cg, hi, N);
+      for (int cg = 0; cg < CG; ++cg) wide_row_stat(st, acc[cg][t], sc, n0 + 32 * cg, hi, N);
       st = stat_merge(st, stat_shfl_xor(st, 32));
       if (hi == 0 && m < M) {
         f32x4 w;
@@ -294,22 +326,23 @@ __global__ __launch_bounds__(256) void gemm_bf16_wide_kernel(
   }
 }
 
-template <int MT, int RING>
+template <int MT, int RING, int NWV, int CG>
 static hipError_t launch_wide_mt(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale, int M,
                                  int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st) {
-  const int nblocks = (N / 16 + 15) / 16;
+  constexpr int WGS = 2 * CG * NWV;
+  const int nblocks = (N / 16 + WGS - 1) / WGS;
   const int nchunks = (Kd / 32 + WIDE_KC - 1) / WIDE_KC;
   const int cps = (nchunks + plan.splits - 1) / plan.splits;
-  dim3 grid(nblocks, plan.splits, 1), block(256);
+  dim3 grid(nblocks, plan.splits, 1), block(64 * NWV);
   const u32x4* W4 = (const u32x4*)Wp;
   if (epi == EPI_PARTIAL)
-    hipLaunchKernelGGL((gemm_bf16_wide_kernel<MT, EPI_PARTIAL, RING>), grid, block, 0, st, X, W4, out,
+    hipLaunchKernelGGL((gemm_bf16_wide_kernel<MT, EPI_PARTIAL, RING, NWV, CG>), grid, block, 0, st, X, W4, out,
                        row_scale, M, N, Kd, cps, nblocks);
   else if (epi == EPI_SWIGLU)
-    hipLaunchKernelGGL((gemm_bf16_wide_kernel<MT, EPI_SWIGLU, RING>), grid, block, 0, st, X, W4, out,
+    hipLaunchKernelGGL((gemm_bf16_wide_kernel<MT, EPI_SWIGLU, RING, NWV, CG>), grid, block, 0, st, X, W4, out,
                        row_scale, M, N, Kd, cps, nblocks);
   else
-    hipLaunchKernelGGL((gemm_bf16_wide_kernel<MT, EPI_LMHEAD, RING>), grid, block, 0, st, X, W4, out,
+    hipLaunchKernelGGL((gemm_bf16_wide_kernel<MT, EPI_LMHEAD, RING, NWV, CG>), grid, block, 0, st, X, W4, out,
                        row_scale, M, N, Kd, cps, nblocks);
   return hipGetLastError();
 }
@@ -327,11 +360,12 @@ hipError_t launch_gemm_bf16_wide(const bf16_t* X, const bf16_t* Wp, void* out, c
   const int cps = (nchunks + plan.splits - 1) / plan.splits;
   if ((plan.splits - 1) * cps >= nchunks) return hipErrorInvalidValue;
   switch (plan.wide) {
-    case 5: return launch_wide_mt<5, 5>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 6: return launch_wide_mt<6, 5>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 8: return launch_wide_mt<8, 4>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+    case 5: return launch_wide_mt<5, 5, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+    case 6: return launch_wide_mt<6, 5, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+    case 8: return launch_wide_mt<8, 4, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
   }
   return hipErrorInvalidValue;
 }
 
-int gemm_bf16_wide_lmhead_parts(int N) { return (N / 16 + 15) / 16 * 4; }
+int gemm_bf16_wide_lmhead_parts(int N) { return (N + WIDE_COLS - 1) / WIDE_COLS * WIDE_NWV; }
+int gemm_bf16_wide_cols() { return WIDE_COLS; }
