@@ -380,7 +380,7 @@ def main():
                     "flops_per_launch": lm_flops, "avg_launch_us": lm_ms * 1e3}
     else:
         gu_kernel = ("gemm_f32_kernel" if cfg.dtype != "bf16" else
-                     "gemm_bf16_kernel" if cfg.M <= 128 else "gemm_bf16_wide_kernel")
+                     "gemm_bf16_kernel" if cfg.M <= 80 else "gemm_bf16_wide_kernel")
         roofline = {"kernel": gu_kernel + " (gate/up projection + SwiGLU)",
                     "bound": "hbm", "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": gu_gbs / HBM_PEAK_GBS,

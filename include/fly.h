@@ -129,8 +129,8 @@ const char* fly_strerror(fly_status s);
  *   "gemm_mt_max"  most 16-row activation tiles one workgroup holds: 5 or 9 (default 9)
  *   "gemm_tiled"   0 = the LDS-tiled GEMM above 256 rows (automatic), 1 = never,
  *                  2, 3, 4 or 6 = always, with workgroups of 128, 192, 256 or 384 rows
- *   "gemm_wide"    0 = the weight-streaming GEMM with 32-row tiles for 129..256 rows (automatic),
- *                  1 = never, 5, 6 or 8 = always, with that many 32-row tiles (M must fit)
+ *   "gemm_wide"    0 = the weight-streaming GEMM with 32-row tiles for 81..256 rows (automatic),
+ *                  1 = never, 3, 4, 5, 6 or 8 = always, with that many 32-row tiles (M must fit)
  *   "attn_splits"  cache splits per (sequence, KV head): 1..256; 0 = automatic
  *   "attn_block_tiles"  most 32-row query tiles per workgroup: 1..8; 0 = automatic (8)
  *   "target_wgs"   workgroups a launch aims for (default 256, one per compute unit)

@@ -14,7 +14,7 @@ int g_force_splits = 0;
 int g_target_wgs = 256;
 int g_mt_max = 9;
 int g_tiled = 0;  // 0 automatic, 1 never, 2, 3, 4 or 6: always, with that workgroup shape
-int g_wide = 0;   // 0 automatic (129..256 rows), 1 never, 5, 6 or 8: always, with that many 32-row tiles
+int g_wide = 0;   // 0 automatic (81..256 rows), 1 never, 3, 4, 5, 6 or 8: always, with that many 32-row tiles
 
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 
@@ -86,12 +86,12 @@ GemmPlan plan_gemm_tiled(int M, int N, int Kd, bool allow_split, int forced) {
   return p;
 }
 
-// 129..256 rows: the weight-streaming kernel with 32 x 32 tiles, one workgroup per
+// 81..256 rows: the weight-streaming kernel with 32 x 32 tiles, one workgroup per
 // 256 columns.  Narrow outputs reach one workgroup per compute unit by split-K
 // with at least sixteen 64-wide chunks per split.
 GemmPlan plan_gemm_wide(int M, int N, int Kd, bool allow_split, int forced) {
   GemmPlan p{1, 1, 1, 1, 0, 0};
-  p.wide = forced ? forced : M <= 160 ? 5 : M <= 192 ? 6 : 8;
+  p.wide = forced ? forced : M <= 96 ? 3 : M <= 128 ? 4 : M <= 160 ? 5 : M <= 192 ? 6 : 8;
   if (allow_split) {
     const int cols = gemm_bf16_wide_cols();
     const int wgs = (N + cols - 1) / cols;
@@ -108,10 +108,11 @@ GemmPlan plan_gemm_wide(int M, int N, int Kd, bool allow_split, int forced) {
 }
 
 GemmPlan plan_gemm(int M, int N, int Kd, bool allow_split, bool need_even_nt) {
-  // Measured at the 405B-slice (136 rows) and 70B batch-16 (256 rows) shapes: from 129 to 256 rows
-  // the wide kernel wins or ties for every GEMM of the layer and for the LM head.
-  if (g_wide >= 5 || (g_wide == 0 && g_tiled < 2 && M > 128 && M <= 256))
-    return plan_gemm_wide(M, N, Kd, allow_split, g_wide >= 5 ? g_wide : 0);
+  // Measured at the 70B width for 36..160 rows and at the 405B-slice (136 rows) and 70B batch-16
+  // (256 rows) shapes: up to 80 rows the kernel with 16-row tiles wins, from 81 to 256 rows the
+  // wide kernel wins or ties for every GEMM of the layer and for the LM head.
+  if (g_wide >= 3 || (g_wide == 0 && g_tiled < 2 && M > 80 && M <= 256))
+    return plan_gemm_wide(M, N, Kd, allow_split, g_wide >= 3 ? g_wide : 0);
   if (g_tiled >= 2 || (g_tiled == 0 && M > 128)) return plan_gemm_tiled(M, N, Kd, allow_split, g_tiled);
   GemmPlan p;
   p.tiled = 0;
@@ -436,7 +437,8 @@ fly_status fly_set_tuning(const char* key, int32_t value) {
     if (value != 0 && value != 1 && gemm_bf16_tiled_rows(value) == 0) return FLY_ERR_BAD_SHAPE;
     g_tiled = value;
   } else if (!strcmp(key, "gemm_wide")) {
-    if (value != 0 && value != 1 && value != 5 && value != 6 && value != 8) return FLY_ERR_BAD_SHAPE;
+    if (value != 0 && value != 1 && value != 3 && value != 4 && value != 5 && value != 6 && value != 8)
+      return FLY_ERR_BAD_SHAPE;
     g_wide = value;
   } else if (!strcmp(key, "target_wgs")) {
     if (value < 1) return FLY_ERR_BAD_SHAPE;

@@ -1,4 +1,4 @@
-// Weight-streaming bf16 GEMM for 129..256 activation rows (paper Sec. 2.1,
+// Weight-streaming bf16 GEMM for 81..256 activation rows (paper Sec. 2.1,
 // Algorithm 1 step 2: the layer projections and the LM head of the
 // verification forward when a batch of sequences is verified together, e.g.
 // sixteen sequences with fifteen drafts each).
@@ -12,7 +12,7 @@
 // covers 256 columns: every wave streams the packed weight tiles of its own 32
 // columns straight from global memory into matrix-core operand registers,
 // through a ring of k-chunks, and holds MT accumulator tiles of
-// v_mfma_f32_32x32x16_bf16 (MT = 5, 6 or 8 tiles of 32 rows; weights = A
+// v_mfma_f32_32x32x16_bf16 (MT = 3, 4, 5, 6 or 8 tiles of 32 rows; weights = A
 // operand, activations = B operand, out^T[n, m] = sum_k W[k, n] X[m, k]).  Two
 // waves share a SIMD, so one multiplies while the other waits for its weights.
 // Only the small activation block goes through LDS, copied there by LDS-direct
@@ -347,7 +347,7 @@ static hipError_t launch_wide_mt(const bf16_t* X, const bf16_t* Wp, void* out, c
   return hipGetLastError();
 }
 
-// plan.wide = number of 32-row tiles (5, 6 or 8).
+// plan.wide = number of 32-row tiles (3, 4, 5, 6 or 8).
 hipError_t launch_gemm_bf16_wide(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale, int M,
                                  int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st) {
   // Host-side shape checks: whole 16-column tiles and 32-row k-tiles, all rows
@@ -360,6 +360,8 @@ hipError_t launch_gemm_bf16_wide(const bf16_t* X, const bf16_t* Wp, void* out, c
   const int cps = (nchunks + plan.splits - 1) / plan.splits;
   if ((plan.splits - 1) * cps >= nchunks) return hipErrorInvalidValue;
   switch (plan.wide) {
+    case 3: return launch_wide_mt<3, 7, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+    case 4: return launch_wide_mt<4, 7, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
     case 5: return launch_wide_mt<5, 5, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
     case 6: return launch_wide_mt<6, 5, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
     case 8: return launch_wide_mt<8, 4, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);

@@ -122,6 +122,18 @@ def test_lmhead_bf16(fb, M, d, V):
     check_lmhead(got, ref, 2e-3)
 
 
+def test_lmhead_bf16_nine_tile_streaming_kernel(fb):
+    """81..128 rows through the 16-row-tile kernel (nine tiles per wave), which the planner no
+    longer picks by itself."""
+    fb.fly_set_tuning("gemm_wide", 1)
+    try:
+        for M, d, V in ((100, 256, 2048 + 48), (128, 96, 272)):
+            got, ref = lmhead_case(fb, M, d, V, "bf16", hidden_std=4.0, seed=7)
+            check_lmhead(got, ref, 2e-3)
+    finally:
+        fb.fly_set_tuning("gemm_wide", 0)
+
+
 @pytest.mark.parametrize("M,d,V", [(200, 256, 2048 + 48), (300, 544, 16 * 131), (1088, 512, 4096),
                                    (145, 32, 16), (385, 96, 272)])
 def test_lmhead_bf16_many_rows(fb, M, d, V):
@@ -141,9 +153,10 @@ def test_lmhead_bf16_many_rows(fb, M, d, V):
 
 @pytest.mark.parametrize("M,d,V,tiles", [(129, 256, 2048 + 48, 0), (160, 96, 16 * 131, 5), (161, 544, 1040, 6),
                                          (192, 32, 16, 6), (200, 320, 4096 + 16, 0), (256, 64, 272, 8),
-                                         (97, 160, 528, 5), (140, 128, 256, 8)])
+                                         (97, 160, 528, 5), (140, 128, 256, 8), (81, 256, 2048 + 48, 0),
+                                         (96, 96, 16 * 131, 3), (128, 544, 1040, 4), (110, 64, 272, 0)])
 def test_lmhead_bf16_wide_rows(fb, M, d, V, tiles):
-    """129..256 rows take the weight-streaming kernel with 32 x 32 tiles (5, 6 or 8 row tiles per
+    """81..256 rows take the weight-streaming kernel with 32 x 32 tiles (3 to 8 row tiles per
     wave): ragged last tile, a vocabulary that is not a multiple of the 256-column block, an odd
     number of k-tiles, fewer chunks than the register ring is deep."""
     fb.fly_set_tuning("gemm_wide", tiles)

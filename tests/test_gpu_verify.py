@@ -243,7 +243,9 @@ def test_attention_stage_bf16(hq, hkv, K, block_tiles):
 def test_gateup_swiglu_stage_bf16():
     """The fused gate/up GEMM + SwiGLU alone (ragged M, F not a multiple of the block)."""
     from paper_2511_22972_amd import binding as fb
-    for M, d, F in ((36, 512, 1056), (9, 256, 512), (100, 128, 16 * 37)):
+    for M, d, F in ((36, 512, 1056), (9, 256, 512), (100, 128, 16 * 37), (80, 96, 272)):
+        # 81..128 rows default to the kernel with 32-row tiles: keep its nine-tile sibling covered
+        fb.fly_set_tuning("gemm_wide", 1 if M > 80 else 0)
         x = synth.hash_normal(5, 320, (M, d), 1.0, torch.bfloat16, "cuda")
         wg = synth.hash_normal(5, 321, (d, F), 0.05, torch.bfloat16, "cuda")
         wu = synth.hash_normal(5, 322, (d, F), 0.05, torch.bfloat16, "cuda")
@@ -294,7 +296,8 @@ def test_gateup_swiglu_stage_bf16_wide_rows():
     row-tile count, ragged rows / columns / k-tiles."""
     from paper_2511_22972_amd import binding as fb
     cases = [(129, 256, 1056, 0), (160, 96, 16 * 37, 5), (161, 544, 512, 6), (192, 32, 16, 6),
-             (200, 320, 2048 + 16, 0), (256, 64, 144, 8), (100, 160, 272, 5), (150, 1024, 256, 8)]
+             (200, 320, 2048 + 16, 0), (256, 64, 144, 8), (100, 160, 272, 5), (150, 1024, 256, 8),
+             (81, 256, 1056, 0), (96, 96, 16 * 37, 3), (97, 544, 512, 0), (128, 320, 272, 4), (50, 64, 144, 3)]
     for M, d, F, tiles in cases:
         fb.fly_set_tuning("gemm_wide", tiles)
         x = synth.hash_normal(8, 320, (M, d), 1.0, torch.bfloat16, "cuda")
@@ -322,7 +325,8 @@ def test_projection_partials_bf16_wide_rows():
     more splits asked for than there are chunks)."""
     from paper_2511_22972_amd import binding as fb
     cases = [(136, 4096, 512, 0, 0), (200, 2048, 528, 0, 0), (256, 1056, 1040, 8, 0), (160, 2080, 256, 5, 5),
-             (192, 96, 16, 6, 0), (129, 3072, 272, 0, 7), (150, 1024, 256, 6, 16)]
+             (192, 96, 16, 6, 0), (129, 3072, 272, 0, 7), (150, 1024, 256, 6, 16),
+             (100, 4096, 512, 0, 0), (96, 2080, 528, 3, 3), (128, 1056, 272, 4, 0), (82, 96, 16, 0, 0)]
     for M, Kd, N, tiles, force_splits in cases:
         fb.fly_set_tuning("gemm_wide", tiles)
         fb.fly_set_tuning("gemm_splits", force_splits)
@@ -349,11 +353,13 @@ def test_projection_partials_bf16_wide_rows():
 def test_projection_partials_bf16():
     """Split-K projection GEMM alone, both kernels: the partial sums add up to x W."""
     from paper_2511_22972_amd import binding as fb
+    # (the 100-row case runs with "gemm_wide" = 1 below: the nine-tile sibling of the default kernel)
     cases = [(M, Kd, N, 0) for M, Kd, N in ((36, 1024, 272), (100, 4096, 512), (200, 2048, 528),
                                             (389, 512, 1040), (1088, 1024, 256), (145, 32, 16))]
     cases += [(389, 2048, 528, shape) for shape in (2, 3, 4, 6)]
     for M, Kd, N, shape in cases:
         fb.fly_set_tuning("gemm_tiled", shape)
+        fb.fly_set_tuning("gemm_wide", 1 if 80 < M <= 128 else 0)
         x = synth.hash_normal(7, 330, (M, Kd), 1.0, torch.bfloat16, "cuda")
         w = synth.hash_normal(7, 331, (Kd, N), 0.05, torch.bfloat16, "cuda")
         wp = torch.empty(Kd * N, dtype=torch.bfloat16, device="cuda")
@@ -363,6 +369,7 @@ def test_projection_partials_bf16():
             splits = fb.fly_proj_partial(x, wp, partial, N)
         finally:
             fb.fly_set_tuning("gemm_tiled", 0)
+            fb.fly_set_tuning("gemm_wide", 0)
         torch.cuda.synchronize()
         assert 1 <= splits <= 16
         got = partial[: splits * M * N].view(splits, M, N).double().sum(0).cpu()
