@@ -35,6 +35,14 @@ depth is pinned only up to the stated logit tolerance (see `Numerics`).
                                   (Eq. 12).  Pinned by the fact that with the gate
                                   always strict the output is the target's own
                                   greedy continuation.
+  * drafting with a model      -- Algorithm 1 step 1 with a draft model M_D
+                                  (the paper's own setting: a small model of the
+                                  same family): K greedy tokens of M_D after the
+                                  sequence so far.  `model_draft_greedy` states it
+                                  as K full passes over the growing sequence;
+                                  pinned by an incremental, cache-carrying
+                                  evaluation (causality) and by the lossless
+                                  property of the strict loop.
 """
 from __future__ import annotations
 
@@ -458,6 +466,39 @@ def pld_propose(y: Sequence[int], n_max: int, K: int) -> Tuple[List[int], int]:
                     ext.append(ext[e + i])
                 return ext[L:], n
     return [y[-1]] * K, 0
+
+
+def model_draft_greedy(y: Sequence[int], K: int, embed: torch.Tensor, layers: Sequence[LayerWeights],
+                       g_final: torch.Tensor, w_lm: torch.Tensor,
+                       kv_prefix: Sequence[Tuple[torch.Tensor, torch.Tensor]], first_pos: int, *,
+                       n_q_heads: int, n_kv_heads: int, head_dim: int, rope_theta: float, eps: float,
+                       storage: str = "f32") -> List[int]:
+    """Algorithm 1 step 1 with a draft model M_D: the K tokens M_D emits greedily
+    after the sequence y (Sec. 2.1: the drafter proposes, the target verifies).
+
+    kv_prefix[layer] = (k [P, Hkv, hd], v [P, Hkv, hd]) is M_D's cache of the
+    positions before first_pos (P >= first_pos; only the first first_pos rows are
+    read); M_D itself processes the tokens y[first_pos:].  Draft i is the argmax
+    (Eq. 1, lowest index on ties) of M_D's distribution after y and the drafts so
+    far.  Written as K full passes over the growing block: no cache is carried
+    from one draft to the next.
+    """
+    assert 0 <= first_pos < len(y) and K >= 1
+    prefix = [(k[None, :first_pos], v[None, :first_pos]) for k, v in kv_prefix]
+    toks = [int(t) for t in y[first_pos:]]
+    drafts: List[int] = []
+    for _ in range(K):
+        block = toks + drafts
+        if len(block) < 2:                       # verify_block wants at least one position after y_{-1}
+            block = block + [0]                  # a dummy last position: causal, so it changes nothing before it
+            pos = len(block) - 2
+        else:
+            pos = len(block) - 1
+        out = verify_block(np.asarray([block], dtype=np.int64), embed, layers, g_final, w_lm, prefix, None,
+                           n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, head_dim=head_dim,
+                           rope_theta=rope_theta, eps=eps, theta=2.0, W=0, storage=storage)
+        drafts.append(int(out["argmax"][0, pos]))
+    return drafts
 
 
 def decode_rounds(y0: Sequence[int], kv0: Sequence[Tuple[torch.Tensor, torch.Tensor]],

@@ -153,3 +153,77 @@ def test_loose_loop_bookkeeping_and_cache(tiny):
         L0 = k0.shape[0]
         assert torch.allclose(k[L0:], nk[:n_new], rtol=0, atol=1e-6)
         assert torch.allclose(v[L0:], nv[:n_new], rtol=0, atol=1e-6)
+
+
+# ---------------------------------------------------------------------------
+# Drafting with a model (Algorithm 1 step 1 with a draft model M_D)
+# ---------------------------------------------------------------------------
+DRAFTER = synth.CONFIGS["c1_tiny"].replace(name="tiny_drafter", n_layers=1, d=128, n_q_heads=2, n_kv_heads=1,
+                                           ffn=256, seed=77, logit_gain=20.0)
+
+
+def incremental_greedy(model, cfg, y, K, first_pos):
+    """The same K tokens by carrying the cache: one token per pass through
+    decoder_layer, appending its k, v rows (an independent route: causality
+    makes it equal to the full passes)."""
+    num = O.Numerics(cfg.dtype)
+    kv = [(k[0, :first_pos].clone(), v[0, :first_pos].clone()) for k, v in model["kv_prefix"]]
+    logits = None
+    toks = [int(t) for t in y[first_pos:]]
+    out = []
+    feed = list(toks)
+    while len(out) < K:
+        for t in feed:
+            x = model["embed"][torch.tensor([t])].clone()
+            for li, w in enumerate(model["layers"]):
+                x, k_new, v_new = O.decoder_layer(x, w, kv[li][0], kv[li][1], cfg.n_q_heads, cfg.n_kv_heads,
+                                                  cfg.head_dim, cfg.rope_theta, cfg.rms_eps, num)
+                kv[li] = (torch.cat([kv[li][0], k_new]), torch.cat([kv[li][1], v_new]))
+            xn = num.act(O.rmsnorm(x, model["g_final"], cfg.rms_eps))
+            logits = O.lm_head_logits(xn, model["w_lm"], None)
+        nxt = int(O.decision_statistics(logits)["argmax"][0])
+        out.append(nxt)
+        feed = [nxt]
+    return out
+
+
+def test_model_drafter_equals_incremental_decoding():
+    cfg = DRAFTER.replace(batch=1, kv_len=12)
+    model = oracle_model(cfg)
+    rng = np.random.default_rng(3)
+    for first_pos, n_after in ((11, 2), (12, 1), (9, 4)):
+        y = rng.integers(0, cfg.vocab, size=first_pos + n_after).tolist()
+        prefix = [(k[0], v[0]) for k, v in model["kv_prefix"]]
+        got = O.model_draft_greedy(y, 5, model["embed"], model["layers"], model["g_final"], model["w_lm"], prefix,
+                                   first_pos, n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads,
+                                   head_dim=cfg.head_dim, rope_theta=cfg.rope_theta, eps=cfg.rms_eps,
+                                   storage=cfg.dtype)
+        assert got == incremental_greedy(model, cfg, y, 5, first_pos), (first_pos, n_after)
+
+
+def test_model_drafted_strict_loop_is_lossless():
+    """Whatever model drafts, a strict verifier (theta above every entropy) emits
+    the target's own greedy continuation (the lossless limit the paper starts from)."""
+    tcfg = synth.CONFIGS["c1_tiny"].replace(batch=1, kv_len=10, logit_gain=12.0)
+    dcfg = DRAFTER.replace(batch=1, kv_len=10, vocab=tcfg.vocab)
+    tm, dm = oracle_model(tcfg), oracle_model(dcfg)
+    y0 = np.random.default_rng(9).integers(0, tcfg.vocab, size=11).tolist()
+    dprefix = [(k[0], v[0]) for k, v in dm["kv_prefix"]]
+
+    def drafter(y, K):
+        return O.model_draft_greedy(y, K, dm["embed"], dm["layers"], dm["g_final"], dm["w_lm"], dprefix,
+                                    dcfg.kv_len - 1, n_q_heads=dcfg.n_q_heads, n_kv_heads=dcfg.n_kv_heads,
+                                    head_dim=dcfg.head_dim, rope_theta=dcfg.rope_theta, eps=dcfg.rms_eps,
+                                    storage=dcfg.dtype), 0
+
+    common = dict(n_q_heads=tcfg.n_q_heads, n_kv_heads=tcfg.n_kv_heads, head_dim=tcfg.head_dim,
+                  rope_theta=tcfg.rope_theta, eps=tcfg.rms_eps, storage=tcfg.dtype)
+    kv0 = [(k[0], v[0]) for k, v in tm["kv_prefix"]]
+    strict = O.decode_rounds(y0, kv0, tm["embed"], tm["layers"], tm["g_final"], tm["w_lm"], None, rounds=3, K=4,
+                             n_max=3, theta=2.0, W=0, drafter=drafter, **common)
+    # the target's own greedy decoding: K = 1 rounds whose single draft is always wrong or right -- s tokens kept
+    # either way are the target's argmax chain
+    plain = O.decode_rounds(y0, kv0, tm["embed"], tm["layers"], tm["g_final"], tm["w_lm"], None,
+                            rounds=len(strict["y"]) - len(y0), K=1, n_max=1, theta=2.0, W=0, **common)
+    assert strict["y"] == plain["y"][:len(strict["y"])]
+    assert all(1 <= s <= 5 for s in strict["s"])
