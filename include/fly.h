@@ -237,6 +237,47 @@ fly_status fly_decode_rounds(const fly_model_desc* desc, const fly_weights* w, c
                              void* workspace, size_t workspace_bytes, fly_stream stream);
 
 /*
+ * Drafting with a draft model M_D (Algorithm 1 step 1 in the paper's own setting:
+ * a small model of the target's family proposes, the target verifies).  For every
+ * sequence b with n = ctx_len[b] tokens: the K tokens M_D emits greedily after
+ * them (Eq. 1 with M_D's distribution, lowest index on ties), by K forward passes
+ * of M_D that chain on the device.
+ *   desc, w, kv   the draft model, its packed weights and its OWN cache.  Only the
+ *                 layer pointers and the capacity of kv are used: the rows before
+ *                 position n-2 must be M_D's rows of the sequence so far (or a
+ *                 synthetic prefix); the rows of the last two tokens are computed
+ *                 (again) by every call, then the rows of draft_1..draft_{K-1}.
+ *                 So the cache needs no roll-back after a rejection: whatever the
+ *                 target kept, the next call finds valid rows before its n-2.
+ *   ctx, ctx_len  [device] as in fly_sequences; 2 <= ctx_len[b] <= max_ctx_len (host bound)
+ *   tokens        [device] int32 [B, K+1]: (last token, draft_1..draft_K)
+ * kv->capacity must be at least max_ctx_len + K, else FLY_ERR_KV_CAPACITY.
+ */
+fly_status fly_model_draft_workspace_bytes(const fly_model_desc* desc, int32_t B, int32_t K,
+                                           int32_t max_ctx_len, size_t* bytes);
+fly_status fly_model_draft(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                           const int32_t* ctx, const int32_t* ctx_len, int32_t ctx_capacity,
+                           int32_t max_ctx_len, int32_t B, int32_t K, int32_t* tokens, void* workspace,
+                           size_t workspace_bytes, fly_stream stream);
+
+/*
+ * fly_decode_rounds with the draft model as drafter: every round drafts K tokens
+ * with fly_model_draft, verifies them with the target (forward, row statistics,
+ * loose acceptance) and rolls the sequences and the target's cache forward.
+ * The two models must share the vocabulary.  Bounds as for fly_decode_rounds,
+ * plus draft_kv->capacity >= seq->max_ctx_len + rounds*(K+1) + K.
+ * Workspace: fly_decode_model_workspace_bytes(desc, draft_desc, B, K, kv->max_kv_len + rounds*(K+1)).
+ */
+fly_status fly_decode_model_workspace_bytes(const fly_model_desc* desc, const fly_model_desc* draft_desc,
+                                            int32_t B, int32_t K, int32_t max_kv_len_end, size_t* bytes);
+fly_status fly_decode_rounds_model(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                                   const fly_model_desc* draft_desc, const fly_weights* draft_w,
+                                   const fly_kv_cache* draft_kv, const fly_sequences* seq,
+                                   const float* row_scale, int32_t B, int32_t K, float theta, int32_t W,
+                                   int32_t rounds, void* workspace, size_t workspace_bytes,
+                                   fly_stream stream);
+
+/*
  * Decoder layers [layer_begin, layer_end) applied in place to a residual
  * stream x [device] fp32 [M, d] (the middle of fly_verify_block, exposed for
  * per-layer checks and per-layer timing).  Uses the same workspace.

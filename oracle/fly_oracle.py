@@ -472,7 +472,7 @@ def model_draft_greedy(y: Sequence[int], K: int, embed: torch.Tensor, layers: Se
                        g_final: torch.Tensor, w_lm: torch.Tensor,
                        kv_prefix: Sequence[Tuple[torch.Tensor, torch.Tensor]], first_pos: int, *,
                        n_q_heads: int, n_kv_heads: int, head_dim: int, rope_theta: float, eps: float,
-                       storage: str = "f32") -> List[int]:
+                       storage: str = "f32", return_margins: bool = False):
     """Algorithm 1 step 1 with a draft model M_D: the K tokens M_D emits greedily
     after the sequence y (Sec. 2.1: the drafter proposes, the target verifies).
 
@@ -481,12 +481,14 @@ def model_draft_greedy(y: Sequence[int], K: int, embed: torch.Tensor, layers: Se
     read); M_D itself processes the tokens y[first_pos:].  Draft i is the argmax
     (Eq. 1, lowest index on ties) of M_D's distribution after y and the drafts so
     far.  Written as K full passes over the growing block: no cache is carried
-    from one draft to the next.
+    from one draft to the next.  With return_margins also the top-2 logit margin
+    behind every draft (a comparison may skip what hinges on a near tie).
     """
     assert 0 <= first_pos < len(y) and K >= 1
     prefix = [(k[None, :first_pos], v[None, :first_pos]) for k, v in kv_prefix]
     toks = [int(t) for t in y[first_pos:]]
     drafts: List[int] = []
+    margins: List[float] = []
     for _ in range(K):
         block = toks + drafts
         if len(block) < 2:                       # verify_block wants at least one position after y_{-1}
@@ -498,7 +500,8 @@ def model_draft_greedy(y: Sequence[int], K: int, embed: torch.Tensor, layers: Se
                            n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, head_dim=head_dim,
                            rope_theta=rope_theta, eps=eps, theta=2.0, W=0, storage=storage)
         drafts.append(int(out["argmax"][0, pos]))
-    return drafts
+        margins.append(float(out["margin"][0, pos]))
+    return (drafts, margins) if return_margins else drafts
 
 
 def decode_rounds(y0: Sequence[int], kv0: Sequence[Tuple[torch.Tensor, torch.Tensor]],

@@ -24,6 +24,8 @@ EXPORTS = [
     "fly_workspace_bytes", "fly_lmhead_workspace_bytes", "fly_verify_block", "fly_decoder_layers",
     "fly_lmhead_entropy_argmax", "fly_accept", "fly_attention", "fly_gateup_swiglu", "fly_proj_partial",
     "fly_pld_draft", "fly_decode_workspace_bytes", "fly_decode_rounds",
+    "fly_model_draft_workspace_bytes", "fly_model_draft", "fly_decode_model_workspace_bytes",
+    "fly_decode_rounds_model",
 ]
 
 
@@ -111,6 +113,18 @@ def _load() -> C.CDLL:
                                       C.POINTER(fly_kv_cache), C.POINTER(fly_sequences), C.c_void_p,
                                       C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_int32,
                                       C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.fly_model_draft_workspace_bytes.argtypes = [C.POINTER(fly_model_desc), C.c_int32, C.c_int32, C.c_int32,
+                                                    C.POINTER(C.c_size_t)]
+    lib.fly_model_draft.argtypes = [C.POINTER(fly_model_desc), C.POINTER(fly_weights), C.POINTER(fly_kv_cache),
+                                    C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                    C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.fly_decode_model_workspace_bytes.argtypes = [C.POINTER(fly_model_desc), C.POINTER(fly_model_desc),
+                                                     C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+    lib.fly_decode_rounds_model.argtypes = [C.POINTER(fly_model_desc), C.POINTER(fly_weights),
+                                            C.POINTER(fly_kv_cache), C.POINTER(fly_model_desc),
+                                            C.POINTER(fly_weights), C.POINTER(fly_kv_cache),
+                                            C.POINTER(fly_sequences), C.c_void_p, C.c_int32, C.c_int32,
+                                            C.c_float, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
     for name in EXPORTS:
         if name != "fly_strerror":
             getattr(lib, name).restype = C.c_int
@@ -382,6 +396,45 @@ def fly_decode_rounds(model: PackedModel, kv: KVCache, seq: Sequences, row_scale
                                  _ptr(row_scale), kv.B, K, theta, W, ngram_max, rounds, _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream()),
            "fly_decode_rounds")
+    kv.max_kv_len += rounds * (K + 1)
+    seq.max_ctx_len += rounds * (K + 1)
+
+
+def fly_model_draft_workspace_bytes(desc: fly_model_desc, B: int, K: int, max_ctx_len: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib.fly_model_draft_workspace_bytes(C.byref(desc), B, K, max_ctx_len, C.byref(out)),
+           "fly_model_draft_workspace_bytes")
+    return out.value
+
+
+def fly_model_draft(draft_model: PackedModel, draft_kv: KVCache, ctx: torch.Tensor, ctx_len: torch.Tensor,
+                    max_ctx_len: int, K: int, tokens: torch.Tensor, workspace: torch.Tensor) -> None:
+    """K greedy tokens of the draft model after every sequence; tokens [B, K+1] int32."""
+    B, cap = ctx.shape
+    kvs = draft_kv.struct()
+    _check(lib.fly_model_draft(C.byref(draft_model.desc), C.byref(draft_model.weights_c), C.byref(kvs),
+                               _ptr(ctx), _ptr(ctx_len), cap, max_ctx_len, B, K, _ptr(tokens), _ptr(workspace),
+                               workspace.numel() * workspace.element_size(), _stream()), "fly_model_draft")
+
+
+def fly_decode_model_workspace_bytes(desc: fly_model_desc, draft_desc: fly_model_desc, B: int, K: int,
+                                     max_kv_len_end: int) -> int:
+    out = C.c_size_t(0)
+    _check(lib.fly_decode_model_workspace_bytes(C.byref(desc), C.byref(draft_desc), B, K, max_kv_len_end,
+                                                C.byref(out)), "fly_decode_model_workspace_bytes")
+    return out.value
+
+
+def fly_decode_rounds_model(model: PackedModel, kv: KVCache, draft_model: PackedModel, draft_kv: KVCache,
+                            seq: Sequences, row_scale: Optional[torch.Tensor], K: int, theta: float, W: int,
+                            rounds: int, workspace: torch.Tensor) -> None:
+    """`rounds` rounds with the draft model as drafter; moves the host-side bounds along."""
+    kvs, dkvs, ss = kv.struct(), draft_kv.struct(), seq.struct()
+    _check(lib.fly_decode_rounds_model(C.byref(model.desc), C.byref(model.weights_c), C.byref(kvs),
+                                       C.byref(draft_model.desc), C.byref(draft_model.weights_c), C.byref(dkvs),
+                                       C.byref(ss), _ptr(row_scale), kv.B, K, theta, W, rounds, _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(), _stream()),
+           "fly_decode_rounds_model")
     kv.max_kv_len += rounds * (K + 1)
     seq.max_ctx_len += rounds * (K + 1)
 

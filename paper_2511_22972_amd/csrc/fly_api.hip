@@ -345,25 +345,109 @@ fly_status run_layers(const fly_model_desc* desc, const fly_weights* w, const fl
   return FLY_OK;
 }
 
-// The step itself on a carved workspace (arguments already validated).
-fly_status run_verify(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
-                      const int32_t* tokens, const float* row_scale, int B, int K, float theta, int W,
-                      const fly_verify_out* out, const Workspace& ws, const Plans& pl, hipStream_t st) {
+// The forward of the step on a carved workspace (arguments already validated): embedding, layers,
+// final norm, LM head with fused statistics.  K = 0 (one position per sequence) is allowed here.
+fly_status run_forward(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                       const int32_t* tokens, const float* row_scale, int B, int K, int32_t* argmax,
+                       float* p_top1, float* h_norm, float* lse, float* hidden_out, const Workspace& ws,
+                       const Plans& pl, hipStream_t st) {
   const int M = B * (K + 1), d = desc->d, dt = desc->dtype;
   HIP_TRY(launch_rope_table(kv->kv_len, ws.rope, B, K, desc->head_dim, desc->rope_theta, st));
   HIP_TRY(launch_embed(tokens, w->embed, dt, ws.x, M, d, desc->vocab, st));
   const void* first_gain = desc->n_layers > 0 ? w->layers[0].g_attn : w->g_final;
   HIP_TRY(launch_reduce_residual_norm(ws.x, nullptr, 0, first_gain, ws.xn, dt, M, d, desc->rms_eps, st));
   FLY_TRY(run_layers(desc, w, kv, ws, pl, 0, desc->n_layers, B, K, st));
-  if (out->hidden_out)
-    HIP_TRY(hipMemcpyAsync(out->hidden_out, ws.x, (size_t)M * d * 4, hipMemcpyDeviceToDevice, st));
+  if (hidden_out)
+    HIP_TRY(hipMemcpyAsync(hidden_out, ws.x, (size_t)M * d * 4, hipMemcpyDeviceToDevice, st));
   // LM head with fused statistics: logits stay in registers
   FLY_TRY(run_gemm(dt, ws.xn, w->w_lm, ws.lm_partial, row_scale, M, desc->vocab, d, pl.lm, EPI_LMHEAD, st));
-  HIP_TRY(launch_lmhead_combine(ws.lm_partial, pl.lm_parts, M, desc->vocab, out->argmax, out->p_top1,
-                                out->h_norm, out->lse, st));
-  // acceptance rule on (draft, argmax, h)
+  HIP_TRY(launch_lmhead_combine(ws.lm_partial, pl.lm_parts, M, desc->vocab, argmax, p_top1, h_norm, lse, st));
+  return FLY_OK;
+}
+
+// The step itself: forward, then the acceptance rule on (draft, argmax, h).
+fly_status run_verify(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                      const int32_t* tokens, const float* row_scale, int B, int K, float theta, int W,
+                      const fly_verify_out* out, const Workspace& ws, const Plans& pl, hipStream_t st) {
+  FLY_TRY(run_forward(desc, w, kv, tokens, row_scale, B, K, out->argmax, out->p_top1, out->h_norm, out->lse,
+                      out->hidden_out, ws, pl, st));
   HIP_TRY(launch_accept(tokens + 1, K + 1, out->argmax, out->h_norm, kv->kv_len, B, K, theta, W,
                         out->accept_len, out->next_token, out->n_loose, out->kv_len_out, st));
+  return FLY_OK;
+}
+
+// Buffers of the model drafter (behind its forward workspace).
+struct DraftScratch {
+  int32_t *tok2, *len_steps, *drafts, *argmax2;
+  float *p_top1, *h_norm;
+  size_t bytes;
+};
+void carve_draft(int B, int K, void* base, DraftScratch* ds) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    void* p = base ? (void*)((char*)base + off) : nullptr;
+    off += round_up(bytes, 256);
+    return p;
+  };
+  ds->tok2 = (int32_t*)take((size_t)2 * B * 4);
+  ds->len_steps = (int32_t*)take((size_t)K * B * 4);
+  ds->drafts = (int32_t*)take((size_t)K * B * 4);
+  ds->argmax2 = (int32_t*)take((size_t)2 * B * 4);
+  ds->p_top1 = (float*)take((size_t)2 * B * 4);
+  ds->h_norm = (float*)take((size_t)2 * B * 4);
+  ds->bytes = off;
+}
+
+// The drafter's cache: layer pointers and capacity only (its lengths follow from the sequences).
+fly_status check_draft_kv(const fly_model_desc* desc, const fly_kv_cache* kv, int64_t max_rows) {
+  if (!kv) return FLY_ERR_NULL_POINTER;
+  if (desc->n_layers > 0 && (!kv->k_layers || !kv->v_layers)) return FLY_ERR_NULL_POINTER;
+  if (kv->capacity < 64 || kv->capacity % 64 != 0) return FLY_ERR_BAD_SHAPE;
+  if (max_rows > kv->capacity) return FLY_ERR_KV_CAPACITY;
+  for (int l = 0; l < desc->n_layers; ++l) {
+    if (!kv->k_layers[l] || !kv->v_layers[l]) return FLY_ERR_NULL_POINTER;
+    if (!aligned16(kv->k_layers[l]) || !aligned16(kv->v_layers[l])) return FLY_ERR_ALIGNMENT;
+  }
+  return FLY_OK;
+}
+
+// K greedy passes of the draft model on carved buffers (arguments already validated):
+// pass 1 over the last two tokens of every sequence, passes 2..K over one draft each.
+fly_status run_model_draft(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                           const int32_t* ctx, const int32_t* ctx_len, int ctx_capacity, int B, int K,
+                           int32_t* tokens, const Workspace& ws2, const Plans& pl2, const Workspace& ws1,
+                           const Plans& pl1, const DraftScratch& ds, hipStream_t st) {
+  HIP_TRY(launch_draft_prepare(ctx, ctx_len, ctx_capacity, B, K, ds.tok2, ds.len_steps, st));
+  fly_kv_cache kvs = *kv;
+  kvs.kv_len = ds.len_steps;
+  FLY_TRY(run_forward(desc, w, &kvs, ds.tok2, nullptr, B, 1, ds.argmax2, ds.p_top1, ds.h_norm, nullptr, nullptr,
+                      ws2, pl2, st));
+  HIP_TRY(launch_draft_pick(ds.argmax2, B, ds.drafts, st));
+  for (int i = 2; i <= K; ++i) {
+    kvs.kv_len = ds.len_steps + (int64_t)(i - 1) * B;
+    FLY_TRY(run_forward(desc, w, &kvs, ds.drafts + (int64_t)(i - 2) * B, nullptr, B, 0,
+                        ds.drafts + (int64_t)(i - 1) * B, ds.p_top1, ds.h_norm, nullptr, nullptr, ws1, pl1, st));
+  }
+  HIP_TRY(launch_draft_assemble(ds.tok2, ds.drafts, B, K, tokens, st));
+  return FLY_OK;
+}
+
+// Plans and workspace of the drafter's two pass shapes (two rows / one row per sequence); the two
+// workspaces occupy the same memory, the scratch follows.
+struct DraftSetup {
+  Plans pl2, pl1;
+  Workspace ws2, ws1;
+  DraftScratch ds;
+  size_t bytes;
+};
+fly_status setup_draft(const fly_model_desc* desc, int B, int K, int max_kv_len, void* base, DraftSetup* s) {
+  FLY_TRY(make_plans(desc, B, 1, max_kv_len, &s->pl2));
+  FLY_TRY(make_plans(desc, B, 0, max_kv_len, &s->pl1));
+  carve(desc, B, 1, s->pl2, base, &s->ws2);
+  carve(desc, B, 0, s->pl1, base, &s->ws1);
+  const size_t fwd = s->ws2.bytes > s->ws1.bytes ? s->ws2.bytes : s->ws1.bytes;
+  carve_draft(B, K, base ? (char*)base + fwd : nullptr, &s->ds);
+  s->bytes = fwd + s->ds.bytes;
   return FLY_OK;
 }
 
@@ -696,6 +780,101 @@ fly_status fly_decode_rounds(const fly_model_desc* desc, const fly_weights* w, c
     int32_t* trace_row = seq->accept_trace ? seq->accept_trace + (int64_t)r * B : nullptr;
     HIP_TRY(launch_pld_draft(seq->ctx, seq->ctx_len, seq->ctx_capacity, B, K, ngram_max, ds.tokens,
                              ngram_row, st));
+    FLY_TRY(run_verify(desc, w, &kvr, ds.tokens, row_scale, B, K, theta, W, &out, ws, pl, st));
+    HIP_TRY(launch_roll_forward(seq->ctx, seq->ctx_len, seq->kv_len, seq->ctx_capacity, B, K, ds.tokens,
+                                ds.accept_len, ds.next_token, ds.kv_len_out, ds.n_loose,
+                                seq->accepted_total, seq->rounds_done, seq->loose_total, trace_row, st));
+  }
+  return FLY_OK;
+}
+
+fly_status fly_model_draft_workspace_bytes(const fly_model_desc* desc, int32_t B, int32_t K,
+                                           int32_t max_ctx_len, size_t* bytes) {
+  if (!bytes) return FLY_ERR_NULL_POINTER;
+  FLY_TRY(check_desc(desc));
+  FLY_TRY(check_block(B, K));
+  if (max_ctx_len < 2) return FLY_ERR_BAD_SHAPE;
+  DraftSetup ds;
+  FLY_TRY(setup_draft(desc, B, K, max_ctx_len + K, nullptr, &ds));
+  *bytes = ds.bytes;
+  return FLY_OK;
+}
+
+fly_status fly_model_draft(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                           const int32_t* ctx, const int32_t* ctx_len, int32_t ctx_capacity,
+                           int32_t max_ctx_len, int32_t B, int32_t K, int32_t* tokens, void* workspace,
+                           size_t workspace_bytes, fly_stream stream) {
+  FLY_TRY(check_desc(desc));
+  FLY_TRY(check_block(B, K));
+  if (!ctx || !ctx_len || !tokens) return FLY_ERR_NULL_POINTER;
+  if (max_ctx_len < 2 || max_ctx_len > ctx_capacity) return FLY_ERR_BAD_SHAPE;
+  FLY_TRY(check_weights(desc, w, 0, desc->n_layers, true));
+  FLY_TRY(check_draft_kv(desc, kv, (int64_t)max_ctx_len + K));
+  DraftSetup ds;
+  FLY_TRY(setup_draft(desc, B, K, max_ctx_len + K, nullptr, &ds));
+  if (!workspace || workspace_bytes < ds.bytes) return FLY_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return FLY_ERR_ALIGNMENT;
+  FLY_TRY(setup_draft(desc, B, K, max_ctx_len + K, workspace, &ds));
+  return run_model_draft(desc, w, kv, ctx, ctx_len, ctx_capacity, B, K, tokens, ds.ws2, ds.pl2, ds.ws1, ds.pl1,
+                         ds.ds, (hipStream_t)stream);
+}
+
+fly_status fly_decode_model_workspace_bytes(const fly_model_desc* desc, const fly_model_desc* draft_desc,
+                                            int32_t B, int32_t K, int32_t max_kv_len_end, size_t* bytes) {
+  if (!bytes) return FLY_ERR_NULL_POINTER;
+  size_t target = 0, drafter = 0;
+  FLY_TRY(fly_decode_workspace_bytes(desc, B, K, max_kv_len_end, &target));
+  FLY_TRY(fly_model_draft_workspace_bytes(draft_desc, B, K, max_kv_len_end + 1, &drafter));
+  *bytes = target + drafter;
+  return FLY_OK;
+}
+
+fly_status fly_decode_rounds_model(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                                   const fly_model_desc* draft_desc, const fly_weights* draft_w,
+                                   const fly_kv_cache* draft_kv, const fly_sequences* seq,
+                                   const float* row_scale, int32_t B, int32_t K, float theta, int32_t W,
+                                   int32_t rounds, void* workspace, size_t workspace_bytes,
+                                   fly_stream stream) {
+  FLY_TRY(check_desc(desc));
+  FLY_TRY(check_desc(draft_desc));
+  FLY_TRY(check_block(B, K));
+  if (W < 0) return FLY_ERR_WINDOW;
+  if (theta != theta) return FLY_ERR_THETA;
+  if (!seq || !seq->ctx || !seq->ctx_len || !seq->kv_len) return FLY_ERR_NULL_POINTER;
+  if (rounds < 0 || seq->ctx_capacity < 2 || seq->max_ctx_len < 2) return FLY_ERR_BAD_SHAPE;
+  if (draft_desc->vocab != desc->vocab) return FLY_ERR_BAD_SHAPE;  // one token alphabet
+  FLY_TRY(check_weights(desc, w, 0, desc->n_layers, true));
+  FLY_TRY(check_weights(draft_desc, draft_w, 0, draft_desc->n_layers, true));
+  FLY_TRY(check_kv(desc, kv, K, 0, desc->n_layers));
+  if (kv->kv_len != seq->kv_len) return FLY_ERR_BAD_SHAPE;
+  const int64_t grow = (int64_t)rounds * (K + 1);
+  if ((int64_t)kv->max_kv_len + grow > kv->capacity) return FLY_ERR_KV_CAPACITY;
+  if ((int64_t)seq->max_ctx_len + grow > seq->ctx_capacity) return FLY_ERR_KV_CAPACITY;
+  const int max_ctx_end = seq->max_ctx_len + (int32_t)grow;
+  FLY_TRY(check_draft_kv(draft_desc, draft_kv, (int64_t)max_ctx_end + K));
+  fly_kv_cache kvr = *kv;
+  kvr.max_kv_len = kv->max_kv_len + (int32_t)(rounds > 0 ? grow - (K + 1) : 0);
+  Plans pl;
+  FLY_TRY(make_plans(desc, B, K, kv->max_kv_len + (int32_t)grow, &pl));
+  Workspace ws;
+  carve(desc, B, K, pl, nullptr, &ws);
+  DecodeScratch ds;
+  carve_decode(B, K, nullptr, &ds);
+  DraftSetup dr;
+  FLY_TRY(setup_draft(draft_desc, B, K, max_ctx_end + K, nullptr, &dr));
+  const size_t target_bytes = round_up(ws.bytes + ds.bytes, 256);
+  if (!workspace || workspace_bytes < target_bytes + dr.bytes) return FLY_ERR_WORKSPACE;
+  if (!aligned16(workspace)) return FLY_ERR_ALIGNMENT;
+  carve(desc, B, K, pl, workspace, &ws);
+  carve_decode(B, K, (char*)workspace + ws.bytes, &ds);
+  FLY_TRY(setup_draft(draft_desc, B, K, max_ctx_end + K, (char*)workspace + target_bytes, &dr));
+  fly_verify_out out{ds.accept_len, ds.next_token, ds.kv_len_out, ds.argmax, ds.h_norm, ds.p_top1,
+                     nullptr, ds.n_loose, nullptr};
+  hipStream_t st = (hipStream_t)stream;
+  for (int r = 0; r < rounds; ++r) {
+    int32_t* trace_row = seq->accept_trace ? seq->accept_trace + (int64_t)r * B : nullptr;
+    FLY_TRY(run_model_draft(draft_desc, draft_w, draft_kv, seq->ctx, seq->ctx_len, seq->ctx_capacity, B, K,
+                            ds.tokens, dr.ws2, dr.pl2, dr.ws1, dr.pl1, dr.ds, st));
     FLY_TRY(run_verify(desc, w, &kvr, ds.tokens, row_scale, B, K, theta, W, &out, ws, pl, st));
     HIP_TRY(launch_roll_forward(seq->ctx, seq->ctx_len, seq->kv_len, seq->ctx_capacity, B, K, ds.tokens,
                                 ds.accept_len, ds.next_token, ds.kv_len_out, ds.n_loose,

@@ -203,6 +203,11 @@ hipError_t launch_attention_f32(const float* q, const float* kcache, const float
 // Decode loop (prompt-lookup drafter, end-of-round bookkeeping).
 hipError_t launch_pld_draft(const int32_t* ctx, const int32_t* ctx_len, int ctx_capacity, int B, int K,
                             int n_max, int32_t* tokens, int32_t* ngram, hipStream_t st);
+hipError_t launch_draft_prepare(const int32_t* ctx, const int32_t* ctx_len, int ctx_capacity, int B, int K,
+                                int32_t* tok2, int32_t* len_steps, hipStream_t st);
+hipError_t launch_draft_pick(const int32_t* argmax2, int B, int32_t* first, hipStream_t st);
+hipError_t launch_draft_assemble(const int32_t* tok2, const int32_t* drafts, int B, int K, int32_t* tokens,
+                                 hipStream_t st);
 hipError_t launch_roll_forward(int32_t* ctx, int32_t* ctx_len, int32_t* kv_len, int ctx_capacity, int B,
                                int K, const int32_t* tokens, const int32_t* accept_len,
                                const int32_t* next_token, const int32_t* kv_len_out,

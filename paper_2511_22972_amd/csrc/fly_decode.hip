@@ -125,3 +125,61 @@ hipError_t launch_roll_forward(int32_t* ctx, int32_t* ctx_len, int32_t* kv_len, 
                      rounds_done, loose_total, trace_row);
   return hipGetLastError();
 }
+
+// ---------------------------------------------------------------------------
+// Drafting with a draft model (Algorithm 1 step 1 with a model M_D): K greedy
+// forward passes of the drafter per round.  These kernels only move token ids
+// and cache lengths between the passes, so that the passes chain on the device.
+//
+// Sequence b has n = ctx_len[b] tokens; the drafter's cache holds valid rows for
+// the positions before n-2 (the rows of the last two tokens are computed again
+// every round: the last one is new, and the one before it is the only row that
+// may be missing, namely after a round that kept all K drafts).  Pass 1 takes
+// the two tokens ctx[n-2], ctx[n-1] against n-2 cached rows; pass i >= 2 takes
+// draft i-1 against n+i-2 rows.
+// ---------------------------------------------------------------------------
+__global__ void draft_prepare_kernel(const int32_t* __restrict__ ctx, const int32_t* __restrict__ ctx_len,
+                                     int ctx_capacity, int B, int K, int32_t* __restrict__ tok2,
+                                     int32_t* __restrict__ len_steps) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  int n = ctx_len[b];
+  n = n < 2 ? 2 : (n > ctx_capacity ? ctx_capacity : n);  // the host rules both out; never read outside the row
+  const int32_t* y = ctx + (int64_t)b * ctx_capacity;
+  tok2[2 * b] = y[n - 2];
+  tok2[2 * b + 1] = y[n - 1];
+  len_steps[b] = n - 2;
+  for (int j = 1; j < K; ++j) len_steps[(int64_t)j * B + b] = n + j - 1;
+}
+
+// drafts[0][b] = argmax of the second row of pass 1
+__global__ void draft_pick_kernel(const int32_t* __restrict__ argmax2, int B, int32_t* __restrict__ first) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b < B) first[b] = argmax2[2 * b + 1];
+}
+
+// tokens[b] = (y_{-1}, draft_1..draft_K), the block the verification step takes
+__global__ void draft_assemble_kernel(const int32_t* __restrict__ tok2, const int32_t* __restrict__ drafts,
+                                      int B, int K, int32_t* __restrict__ tokens) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  int32_t* out = tokens + (int64_t)b * (K + 1);
+  out[0] = tok2[2 * b + 1];
+  for (int i = 0; i < K; ++i) out[1 + i] = drafts[(int64_t)i * B + b];
+}
+
+hipError_t launch_draft_prepare(const int32_t* ctx, const int32_t* ctx_len, int ctx_capacity, int B, int K,
+                                int32_t* tok2, int32_t* len_steps, hipStream_t st) {
+  hipLaunchKernelGGL(draft_prepare_kernel, dim3((B + 63) / 64), dim3(64), 0, st, ctx, ctx_len, ctx_capacity, B,
+                     K, tok2, len_steps);
+  return hipGetLastError();
+}
+hipError_t launch_draft_pick(const int32_t* argmax2, int B, int32_t* first, hipStream_t st) {
+  hipLaunchKernelGGL(draft_pick_kernel, dim3((B + 63) / 64), dim3(64), 0, st, argmax2, B, first);
+  return hipGetLastError();
+}
+hipError_t launch_draft_assemble(const int32_t* tok2, const int32_t* drafts, int B, int K, int32_t* tokens,
+                                 hipStream_t st) {
+  hipLaunchKernelGGL(draft_assemble_kernel, dim3((B + 63) / 64), dim3(64), 0, st, tok2, drafts, B, K, tokens);
+  return hipGetLastError();
+}

@@ -189,3 +189,52 @@ def test_decode_argument_checks(fb):
     assert g(*args(seq=C.byref(seq_other))) == -2                   # cache lengths must be one array
     assert g(*args(ws=None)) == -9
     assert g(*args(wsb=out.value - 1)) == -9
+
+
+def test_model_draft_argument_checks(fb):
+    p = C.c_void_p(4096)
+    d = _desc(fb)
+    out = C.c_size_t(0)
+    q = fb.lib.fly_model_draft_workspace_bytes
+    assert q(C.byref(d), 2, 4, 64, C.byref(out)) == 0 and out.value > 0
+    need = out.value
+    assert q(C.byref(d), 2, 4, 64, None) == -1
+    assert q(C.byref(d), 2, 0, 64, C.byref(out)) == -3
+    assert q(C.byref(d), 2, 4, 1, C.byref(out)) == -2               # a sequence needs two tokens
+    lw = (fb.fly_layer_weights * 2)(*[fb.fly_layer_weights(4096, 4096, 4096, 4096, 4096, 4096)] * 2)
+    w = fb.fly_weights(4096, lw, 4096, 4096)
+    karr = (C.c_void_p * 2)(4096, 4096)
+    kv = fb.fly_kv_cache(karr, karr, None, 128, 0)                   # the drafter's cache needs no length array
+    f = fb.lib.fly_model_draft
+    args = lambda **kw: [C.byref(d), C.byref(w), kw.get("kv", C.byref(kv)), kw.get("ctx", p), p, kw.get("cap", 100),
+                         kw.get("maxlen", 64), 2, kw.get("K", 4), kw.get("tok", p), kw.get("ws", 4096),
+                         kw.get("wsb", need), None]
+    assert f(*args(ctx=None)) == -1
+    assert f(*args(tok=None)) == -1
+    assert f(*args(K=64)) == -3
+    assert f(*args(maxlen=1)) == -2
+    assert f(*args(maxlen=101)) == -2                                # bound beyond the token rows
+    kv_small = fb.fly_kv_cache(karr, karr, None, 64, 0)
+    assert f(*args(kv=C.byref(kv_small))) == -10                     # 64 + 4 rows do not fit 64
+    assert f(*args(ws=None)) == -9
+    assert f(*args(wsb=need - 1)) == -9
+    # the loop with a draft model: one vocabulary, room in both caches
+    tq = fb.lib.fly_decode_model_workspace_bytes
+    assert tq(C.byref(d), C.byref(d), 2, 4, 128, C.byref(out)) == 0
+    both = out.value
+    tkv = fb.fly_kv_cache(karr, karr, 4096, 192, 100)
+    seq = fb.fly_sequences(4096, 4096, 4096, 256, 101, None, None, None, None, None)
+    dkv = fb.fly_kv_cache(karr, karr, None, 192, 0)
+    g = fb.lib.fly_decode_rounds_model
+    gargs = lambda **kw: [C.byref(d), C.byref(w), C.byref(tkv), kw.get("dd", C.byref(d)), C.byref(w),
+                          kw.get("dkv", C.byref(dkv)), kw.get("seq", C.byref(seq)), None, 2, kw.get("K", 4), 0.3,
+                          kw.get("W", 6), kw.get("rounds", 3), kw.get("ws", 4096), kw.get("wsb", both), None]
+    assert g(*gargs(seq=None)) == -1
+    assert g(*gargs(K=0)) == -3
+    assert g(*gargs(W=-1)) == -4
+    other = _desc(fb, vocab=4096)
+    assert g(*gargs(dd=C.byref(other))) == -2                        # two alphabets
+    assert g(*gargs(rounds=19)) == -10                               # the target's cache is too short
+    dkv_small = fb.fly_kv_cache(karr, karr, None, 64, 0)
+    assert g(*gargs(dkv=C.byref(dkv_small))) == -10                  # the drafter's cache is too short
+    assert g(*gargs(wsb=both - 1)) == -9

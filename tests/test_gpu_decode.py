@@ -171,3 +171,126 @@ def test_decode_rounds_limits():
     with pytest.raises(fb.FlyError) as e:                        # the rows cannot hold that many rounds
         fb.fly_decode_rounds(wl.model, wl.kv, seq, None, 4, 0.3, 6, 3, 200, ws)
     assert e.value.status == -10
+
+
+# ---------------------------------------------------------------------------
+# Drafting with a draft model; the loop with the model as drafter
+# ---------------------------------------------------------------------------
+DRAFT_F32 = C1.replace(name="tiny_drafter", n_layers=1, d=128, n_q_heads=2, n_kv_heads=1, ffn=256, seed=77)
+DRAFT_B16 = B16_SMALL.replace(name="bf16_drafter", n_layers=1, d=128, n_q_heads=2, n_kv_heads=1, ffn=256, seed=78)
+
+
+def oracle_drafts(dcfg, dmodel, b, y, K, first_pos):
+    prefix = [(k[b], v[b]) for k, v in dmodel["kv_prefix"]]
+    return O.model_draft_greedy(y, K, dmodel["embed"], dmodel["layers"], dmodel["g_final"], dmodel["w_lm"], prefix,
+                                first_pos, n_q_heads=dcfg.n_q_heads, n_kv_heads=dcfg.n_kv_heads,
+                                head_dim=dcfg.head_dim, rope_theta=dcfg.rope_theta, eps=dcfg.rms_eps,
+                                storage=dcfg.dtype, return_margins=True)
+
+
+@pytest.mark.parametrize("dcfg,K", [(DRAFT_F32, 5), (DRAFT_B16, 4), (DRAFT_B16, 1)])
+def test_model_draft_matches_oracle(dcfg, K):
+    """fly_model_draft: K chained forward passes of the draft model give the oracle's greedy tokens
+    (up to the first draft that hinges on a near tie), for ragged sequence lengths."""
+    from paper_2511_22972_amd import binding as fb
+    lens = [37, 2, 19, 64]                                    # tokens per sequence (>= 2)
+    dcfg = dcfg.replace(batch=len(lens), kv_len=70, K=K)
+    wl = GpuWorkload(dcfg, kv_lens=[n - 1 for n in lens], capacity=128)
+    prompts = make_prompts(dcfg, lens, seed=31)
+    ctx = torch.zeros(len(lens), 80, dtype=torch.int32)
+    for b, r in enumerate(prompts):
+        ctx[b, :len(r)] = torch.tensor(r, dtype=torch.int32)
+    ctx_d = ctx.cuda()
+    len_d = torch.tensor(lens, dtype=torch.int32).cuda()
+    tokens = torch.full((len(lens), K + 1), -1, dtype=torch.int32, device="cuda")
+    ws = fb.alloc_workspace(fb.fly_model_draft_workspace_bytes(wl.desc, len(lens), K, max(lens)))
+    fb.fly_model_draft(wl.model, wl.kv, ctx_d, len_d, max(lens), K, tokens, ws)
+    torch.cuda.synchronize()
+    got = tokens.cpu().numpy()
+    dmodel = oracle_model(dcfg)
+    compared = 0
+    for b, y in enumerate(prompts):
+        drafts, margins = oracle_drafts(dcfg, dmodel, b, y, K, len(y) - 2)
+        assert got[b, 0] == y[-1]
+        for i in range(K):
+            if margins[i] < 1e-3:
+                break
+            assert got[b, 1 + i] == drafts[i], (b, i, got[b], drafts)
+            compared += 1
+    assert compared >= len(lens) * K - 2
+    # a second call on the same state rewrites the same rows: same tokens
+    tokens2 = torch.full_like(tokens, -1)
+    fb.fly_model_draft(wl.model, wl.kv, ctx_d, len_d, max(lens), K, tokens2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(tokens, tokens2)
+
+
+def run_model_loop(tcfg, dcfg, prompts, rounds, K, theta, W):
+    from paper_2511_22972_amd import binding as fb
+    lens = [len(p) - 1 for p in prompts]
+    cap = (max(lens) + rounds * (K + 1) + 2 * K + 2 + 63) // 64 * 64
+    twl = GpuWorkload(tcfg.replace(K=K), kv_lens=lens, capacity=cap)
+    dwl = GpuWorkload(dcfg.replace(K=K), kv_lens=lens, capacity=cap)
+    seq = fb.Sequences(twl.kv, max(len(p) for p in prompts) + rounds * (K + 1) + 3, rounds)
+    seq.set_sequences(prompts)
+    ws = fb.alloc_workspace(fb.fly_decode_model_workspace_bytes(twl.desc, dwl.desc, tcfg.batch, K,
+                                                                max(lens) + rounds * (K + 1)))
+    fb.fly_decode_rounds_model(twl.model, twl.kv, dwl.model, dwl.kv, seq, None, K, theta, W, rounds, ws)
+    torch.cuda.synchronize()
+    return twl, dwl, seq
+
+
+def check_model_loop(tcfg, dcfg, prompts, rounds, K, theta, W):
+    tmodel, dmodel = oracle_model(tcfg), oracle_model(dcfg)
+    twl, dwl, seq = run_model_loop(tcfg, dcfg, prompts, rounds, K, theta, W)
+    trace = seq.accept_trace.cpu().numpy()
+    ctx = seq.ctx.cpu().numpy()
+    compared, kept = 0, 0
+    for b, p in enumerate(prompts):
+        L = len(p) - 1
+
+        def drafter(y, k, b=b, first=len(p) - 2):
+            drafts, margins = oracle_drafts(dcfg, dmodel, b, y, k, first)
+            return drafts, min(margins)                       # the tag slot carries the drafter's smallest margin
+
+        kv0 = [(k[b, :L], v[b, :L]) for k, v in tmodel["kv_prefix"]]
+        res = O.decode_rounds(p, kv0, tmodel["embed"], tmodel["layers"], tmodel["g_final"], tmodel["w_lm"], None,
+                              rounds=rounds, K=K, n_max=1, theta=theta, W=W, drafter=drafter,
+                              n_q_heads=tcfg.n_q_heads, n_kv_heads=tcfg.n_kv_heads, head_dim=tcfg.head_dim,
+                              rope_theta=tcfg.rope_theta, eps=tcfg.rms_eps, storage=tcfg.dtype)
+        good = unambiguous_rounds(res, theta)
+        for r, info in enumerate(res["rounds"][:good]):
+            if info["ngram"] < 1e-3:                          # a draft hinged on a near tie
+                good = r
+                break
+        assert trace[:good, b].tolist() == res["s"][:good], (b, trace[:, b], res["s"])
+        n_tok = len(p) + sum(res["s"][:good])
+        assert ctx[b, :n_tok].tolist() == res["y"][:n_tok], b
+        compared += good
+        kept += sum(s - 1 for s in res["s"][:good])
+        assert seq.ctx_len.cpu()[b] == len(p) + trace[:, b].sum() == twl.kv.kv_len.cpu()[b] + 1
+    print("model-drafted rounds compared", compared, "of", rounds * len(prompts), "kept drafts", kept)
+    return compared, kept
+
+
+def test_decode_rounds_model_fp32():
+    tcfg = C1.replace(batch=3, kv_len=40)
+    dcfg = DRAFT_F32.replace(batch=3, kv_len=40, vocab=tcfg.vocab)
+    prompts = make_prompts(tcfg, [41, 23, 34], seed=41)
+    # (this tiny model's rows are almost uniform: a few rounds hinge on near ties and end the comparison)
+    compared, _ = check_model_loop(tcfg, dcfg, prompts, 5, K=4, theta=2.0, W=6)
+    assert compared >= 8
+    # every mismatch deferred and no window: all K drafts of this unrelated drafter are kept
+    compared, kept = check_model_loop(tcfg, dcfg, prompts, 5, K=5, theta=0.0, W=0)
+    assert compared >= 8 and kept == 5 * compared
+
+
+def test_decode_rounds_model_self_drafting_bf16():
+    """The target as its own drafter: apart from the one cache row the drafter recomputes from
+    the token (the target's synthetic prefix row differs), the drafts are the target's own
+    choices, so most rounds keep all K drafts -- also the case where the drafter lacks the row
+    of the last draft at the next round."""
+    tcfg = B16_SMALL.replace(batch=2, kv_len=60)
+    prompts = make_prompts(tcfg, [61, 30], seed=42)
+    compared, kept = check_model_loop(tcfg, tcfg, prompts, 6, K=3, theta=0.3, W=1)
+    assert compared >= 8 and kept >= 8
