@@ -37,8 +37,10 @@ MEASURED_TRAFFIC_BYTES = {"c3_70b": 946.6e6}
 # The paper's own figure where a preset is its setting (Table 3: Llama-3.1-70B target, K = 15,
 # batch 1, one MI355X).  Context only: its software stack, prefix length and precision are not
 # stated, so vs_baseline stays null.
-PAPER_CONTEXT = {"p70b_k15": {"paper_reference": {"verify_ms_per_round": 58.62, "hardware": "1x MI355X",
-                                                   "source": "Table 3 (target verification)"}}}
+PAPER_CONTEXT = {"p70b_k15": {"paper_reference": {"verify_ms_per_round": 58.62, "draft_ms_per_round": 245.51,
+                                                   "hardware": "1x MI355X",
+                                                   "source": "Table 3 (target verification; 8B drafter without "
+                                                             "the multi-level acceleration)"}}}
 
 
 def log(*a):
@@ -113,6 +115,55 @@ def decode_loop_line(fb, cfg, desc, model, kv, row_scale):
     return {"rounds": DECODE_ROUNDS, "ms_per_round": ms / DECODE_ROUNDS,
             "tokens_per_s": s_sum / (ms * 1e-3), "tau": s_sum / (DECODE_ROUNDS * B),
             "ngram_max": DECODE_NGRAM, "drafter": "prompt lookup on a synthetic prompt"}
+
+
+def model_drafted_loop_line(fb, cfg, desc, model, kv, row_scale):
+    """Algorithm 1 with a draft MODEL as drafter (the paper's own setting: an 8B-shaped drafter for the
+    70B-shaped target): K chained greedy passes of the drafter, the verification step, the roll-forward.
+    Reports the time of the drafting alone and of the whole round.  Only for targets whose vocabulary is
+    the 8B preset's; None otherwise."""
+    dcfg = synth.CONFIGS["c2_8b"]
+    if cfg.dtype != "bf16" or cfg.vocab != dcfg.vocab or cfg.n_layers < 16:
+        return None
+    B, K = cfg.batch, cfg.K
+    rounds, warm = 3, 1
+    dcfg = dcfg.replace(batch=B, K=K, kv_len=cfg.kv_len)
+    ddesc = fb.make_desc(dcfg)
+    dmodel = fb.PackedModel(ddesc, lambda name, layer: synth.make_weight(dcfg, name, layer, "cuda"))
+    n0 = cfg.kv_len + 1
+    cap = (n0 + (rounds + warm + 1) * (K + 1) + K + 63) // 64 * 64
+    dkv = fb.KVCache(ddesc, B, cap)
+    for l in range(dcfg.n_layers):
+        k, v = synth.make_kv_prefix(dcfg, l, "cuda")
+        dkv.load_prefix(l, k, v)
+    seq = fb.Sequences(kv, n0 + (rounds + warm) * (K + 1) + 1, rounds + warm)
+    prompt = synth.hash_tokens(cfg.seed, 951, B * n0, cfg.vocab, "cuda").view(B, n0)
+    seq.ctx[:, :n0] = prompt
+    seq.ctx_len.fill_(n0)
+    seq.max_ctx_len = n0
+    kv.set_lengths([cfg.kv_len] * B)
+    ws = fb.alloc_workspace(fb.fly_decode_model_workspace_bytes(desc, ddesc, B, K, cfg.kv_len + (rounds + warm) * (K + 1)))
+    fb.fly_decode_rounds_model(model, kv, dmodel, dkv, seq, row_scale, K, cfg.theta, cfg.window, warm, ws)
+    torch.cuda.synchronize()
+    s_before = seq.accepted_total.sum().item()
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    fb.fly_decode_rounds_model(model, kv, dmodel, dkv, seq, row_scale, K, cfg.theta, cfg.window, rounds, ws)
+    t1.record()
+    torch.cuda.synchronize()
+    round_ms = t0.elapsed_time(t1) / rounds
+    s_sum = seq.accepted_total.sum().item() - s_before
+    # the drafting alone, on the state the loop left
+    tokens = torch.empty(B, K + 1, dtype=torch.int32, device="cuda")
+    dws = fb.alloc_workspace(fb.fly_model_draft_workspace_bytes(ddesc, B, K, seq.max_ctx_len))
+    draft_ms = time_region(lambda: fb.fly_model_draft(dmodel, dkv, seq.ctx, seq.ctx_len, seq.max_ctx_len, K, tokens, dws),
+                           3, 1)
+    kv.set_lengths([cfg.kv_len] * B)
+    kv.max_kv_len = cfg.kv_len
+    return {"drafter": "c2_8b-shaped model (32 layers, d=4096), greedy", "rounds": rounds,
+            "ms_per_round": round_ms, "draft_ms_per_round": draft_ms, "drafter_passes_per_round": K,
+            "tokens_per_s": s_sum / (round_ms * rounds * 1e-3), "tau": s_sum / (rounds * B),
+            "note": "random weights: the drafter's tokens are unrelated to the target's, tau says nothing about text"}
 
 
 def algorithmic_bytes(cfg):
@@ -402,6 +453,7 @@ def main():
         "gate_up": {"avg_launch_us": gu_ms * 1e3, "achieved_GBps": gu_gbs, "achieved_TFLOPs": gu_flops / (gu_ms * 1e-3) / 1e12},
         "lm_head": lm_head,
         "decode_loop": decode_loop_line(fb, cfg, desc, model, kv, row_scale),
+        "model_drafted_loop": model_drafted_loop_line(fb, cfg, desc, model, kv, row_scale),
         "graph_replay": {"ms_per_step": graph_ms,
                          "note": "the same step captured once in a HIP graph and replayed; equal to the eager time when the device, not the host launch path, is the limit"},
     }
