@@ -26,13 +26,9 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 namespace {
 
 constexpr int WIDE_KC = 2;  // 32-wide k-tiles per chunk (pipeline step)
-#ifndef WIDE_NWV
-#define WIDE_NWV 8
-#endif
-#ifndef WIDE_CG
-#define WIDE_CG 1
-#endif
-#define WIDE_COLS (32 * WIDE_CG * WIDE_NWV)
+constexpr int WIDE_NWV = 8;  // waves per workgroup
+constexpr int WIDE_CG = 1;   // 32-column groups per wave
+constexpr int WIDE_COLS = 32 * WIDE_CG * WIDE_NWV;
 
 __device__ __forceinline__ float silu_w(float x) { return x / (1.f + __expf(-x)); }
 
