@@ -43,6 +43,18 @@ depth is pinned only up to the stated logit tolerance (see `Numerics`).
                                   pinned by an incremental, cache-carrying
                                   evaluation (causality) and by the lossless
                                   property of the strict loop.
+  * sampled target tokens      -- the paper reports results at temperature 1
+                                  (Tables 1-2) but states its rule with the
+                                  argmax only (Eqs. 1-2).  This build's reading:
+                                  y_i is drawn from softmax(l_i / T) and takes
+                                  the argmax's place in Eq. 2; the entropy gate
+                                  reads the same tempered distribution.  The
+                                  draw is the Gumbel-max construction over a
+                                  Philox4x32-10 stream (`sample_rows`).  Pinned by
+                                  the generator's published known-answer vectors,
+                                  by a chi-square test of the draws against the
+                                  softmax probabilities, and by the limits T -> 0
+                                  (the argmax) and a one-hot row.
 """
 from __future__ import annotations
 
@@ -224,6 +236,84 @@ def block_statistics(logits: np.ndarray) -> Dict[str, np.ndarray]:
 
 
 # ==========================================================================
+# 2b. Drawing the target's token at temperature > 0 (this build's reading of
+#     the temperature-1 rows of Tables 1-2: the drawn token replaces the
+#     argmax of Eq. 1 in the match indicator of Eq. 2).
+# ==========================================================================
+
+_PHILOX_M0, _PHILOX_M1 = 0xD2511F53, 0xCD9E8D57
+_PHILOX_W0, _PHILOX_W1 = 0x9E3779B9, 0xBB67AE85
+
+
+def philox4x32_10(counter: np.ndarray, key: Tuple[int, int]) -> np.ndarray:
+    """Philox4x32 with ten rounds (Salmon, Moraes, Dror, Shaw: "Parallel random
+    numbers: as easy as 1, 2, 3", SC 2011).  counter [..., 4] uint32 -> [..., 4] uint32.
+
+    One round: (c0, c1, c2, c3) -> (hi(M1 c2) ^ c1 ^ k0, lo(M1 c2), hi(M0 c0) ^ c3 ^ k1,
+    lo(M0 c0)); the key advances by the Weyl constants between rounds.
+    """
+    c = np.asarray(counter, dtype=np.uint64)
+    c0, c1, c2, c3 = c[..., 0], c[..., 1], c[..., 2], c[..., 3]
+    mask = np.uint64(0xFFFFFFFF)
+    sh = np.uint64(32)
+    k0, k1 = int(key[0]) & 0xFFFFFFFF, int(key[1]) & 0xFFFFFFFF
+    for _ in range(10):
+        p0 = np.uint64(_PHILOX_M0) * c0
+        p1 = np.uint64(_PHILOX_M1) * c2
+        c0, c1, c2, c3 = ((p1 >> sh) ^ c1 ^ np.uint64(k0), p1 & mask,
+                          (p0 >> sh) ^ c3 ^ np.uint64(k1), p0 & mask)
+        k0 = (k0 + _PHILOX_W0) & 0xFFFFFFFF
+        k1 = (k1 + _PHILOX_W1) & 0xFFFFFFFF
+    return np.stack([c0, c1, c2, c3], axis=-1).astype(np.uint32)
+
+
+def sample_bits(M: int, V: int, seed: int, offset: int) -> np.ndarray:
+    """The 32 random bits of every (row m, column v) of one call: word v % 4 of the
+    Philox block with counter (v // 4, m, offset low, offset high) and key
+    (seed low, seed high).  `offset` tells calls with the same seed apart."""
+    nblk = (V + 3) // 4
+    ctr = np.zeros((M, nblk, 4), dtype=np.uint64)
+    ctr[..., 0] = np.arange(nblk, dtype=np.uint64)[None, :]
+    ctr[..., 1] = np.arange(M, dtype=np.uint64)[:, None]
+    ctr[..., 2] = offset & 0xFFFFFFFF
+    ctr[..., 3] = (offset >> 32) & 0xFFFFFFFF
+    bits = philox4x32_10(ctr, (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF))
+    return bits.reshape(M, nblk * 4)[:, :V]
+
+
+def uniform_open01(bits: np.ndarray) -> np.ndarray:
+    """u = (top 23 bits + 1/2) / 2^23, strictly inside (0, 1), exact in float32."""
+    return ((np.asarray(bits, dtype=np.uint32) >> np.uint32(9)).astype(np.float64) + 0.5) * 2.0 ** -23
+
+
+def gumbel_noise(bits: np.ndarray) -> np.ndarray:
+    """Standard Gumbel variates G = -ln(-ln u)."""
+    return -np.log(-np.log(uniform_open01(bits)))
+
+
+def sample_rows(logits: np.ndarray, seed: int, offset: int) -> Dict[str, np.ndarray]:
+    """One draw per row from softmax(logits[m]) by the Gumbel-max construction:
+    argmax_v (l_v + G_v) with independent standard Gumbel G_v is distributed as
+    softmax(l).  The decision is taken in float32 (float32 logits plus float32
+    noise), lowest index on ties.
+
+    token   -- the drawn column per row
+    margin  -- largest minus second-largest perturbed logit (near-tie diagnostic)
+    """
+    l = np.asarray(logits, dtype=np.float64)
+    M, V = l.shape
+    g = gumbel_noise(sample_bits(M, V, seed, offset))
+    z = l.astype(np.float32) + g.astype(np.float32)
+    token = np.argmax(z, axis=1).astype(np.int64)
+    if V > 1:
+        part = np.partition(z.astype(np.float64), V - 2, axis=1)
+        margin = part[:, V - 1] - part[:, V - 2]
+    else:
+        margin = np.full(M, np.inf)
+    return {"token": token, "margin": margin}
+
+
+# ==========================================================================
 # 3. Decoder forward (textbook pre-norm decoder; shapes come from the
 #    workload, the paper only says "a single forward pass", Sec. 2.1).
 # ==========================================================================
@@ -400,8 +490,14 @@ def verify_block(tokens, embed: torch.Tensor, layers: Sequence[LayerWeights],
                  kv_prefix: Sequence[Tuple[torch.Tensor, torch.Tensor]],
                  row_scale: Optional[torch.Tensor], *, n_q_heads: int, n_kv_heads: int,
                  head_dim: int, rope_theta: float, eps: float, theta: float, W: int,
-                 storage: str = "f32", return_logits: bool = False) -> Dict[str, np.ndarray]:
+                 storage: str = "f32", return_logits: bool = False,
+                 sample: Optional[Tuple[int, int]] = None) -> Dict[str, np.ndarray]:
     """The whole verification step for B sequences (Sec. 2.1-2.2, Alg. 1 steps 2-4).
+
+    With sample = (seed, offset) the target's tokens y_1..y_{K+1} are drawn from
+    softmax of the scaled logits (`sample_rows`, row m = b (K+1) + i) instead of
+    being their argmax, and the acceptance rule compares the drafts with the
+    drawn tokens; "sampled" and "sample_margin" are added to the result.
 
     tokens [B, K+1] = (y_{-1}, draft_1..draft_K) per sequence.
     kv_prefix[layer] = (k [B, L, Hkv, hd], v [B, L, Hkv, hd]).
@@ -429,7 +525,13 @@ def verify_block(tokens, embed: torch.Tensor, layers: Sequence[LayerWeights],
     logits = torch.stack(logits_all)  # [B, R, V]
     stats = decision_statistics(logits.reshape(B * R, -1))
     out = {k: v.reshape(B, R) for k, v in stats.items()}
-    acc = accept_block(tokens[:, 1:], out["argmax"], out["h"], theta, W)
+    target = out["argmax"]
+    if sample is not None:
+        drawn = sample_rows(logits.reshape(B * R, -1).numpy(), sample[0], sample[1])
+        out["sampled"] = drawn["token"].reshape(B, R)
+        out["sample_margin"] = drawn["margin"].reshape(B, R)
+        target = out["sampled"]
+    acc = accept_block(tokens[:, 1:], target, out["h"], theta, W)
     out.update(acc)
     out["new_kv"] = new_kv
     if return_logits:

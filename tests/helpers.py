@@ -37,13 +37,14 @@ def row_scale(cfg: synth.VerifyConfig) -> torch.Tensor:
 
 
 def oracle_verify(cfg: synth.VerifyConfig, model: Dict, tokens: np.ndarray, theta=None,
-                  W=None, return_logits=False) -> Dict:
+                  W=None, return_logits=False, sample=None) -> Dict:
     return O.verify_block(
         tokens, model["embed"], model["layers"], model["g_final"], model["w_lm"],
         model["kv_prefix"], row_scale(cfg), n_q_heads=cfg.n_q_heads,
         n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim, rope_theta=cfg.rope_theta,
         eps=cfg.rms_eps, theta=cfg.theta if theta is None else theta,
-        W=cfg.window if W is None else W, storage=cfg.dtype, return_logits=return_logits)
+        W=cfg.window if W is None else W, storage=cfg.dtype, return_logits=return_logits,
+        sample=sample)
 
 
 def draft_chain(cfg: synth.VerifyConfig, model: Dict) -> np.ndarray:
