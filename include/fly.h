@@ -178,6 +178,31 @@ fly_status fly_verify_block(const fly_model_desc* desc, const fly_weights* w, co
                             size_t workspace_bytes, fly_stream stream);
 
 /*
+ * The verification step at temperature > 0.  The paper reports temperature-1
+ * results (Tables 1-2) and states its rule with the argmax only (Eqs. 1-2);
+ * this entry point takes the reading that the target's token y_i is DRAWN from
+ * softmax(row_scale[m] * logits[m]) and takes the argmax's place in the match
+ * indicator of Eq. 2, while the entropy gate (Eqs. 5-6) reads the same tempered
+ * distribution.  Everything else is fly_verify_block.
+ *   seed, offset  the draw of row m = b*(K+1) + i and column v is the Gumbel-max
+ *                 construction, argmax_v (logit_v + G_v), G_v = -ln(-ln u_v), with
+ *                 u_v = (top 23 bits + 1/2) / 2^23 of word v % 4 of the
+ *                 Philox4x32-10 block with counter (v / 4, m, offset low word,
+ *                 offset high word) and key (seed low word, seed high word).  Give
+ *                 every call of a run its own offset (a round counter, say).
+ *   sampled       [device] int32 [B, K+1]: the drawn tokens y_1..y_{K+1}; the
+ *                 acceptance rule compares the drafts with these, next_token is
+ *                 one of them.  out->argmax still receives the argmax.
+ * The logits are still never written to memory: the draw is one more statistic
+ * fused into the LM head.  Same workspace as fly_verify_block.
+ */
+fly_status fly_verify_block_sampled(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                                    const int32_t* tokens, const float* row_scale, int32_t B, int32_t K,
+                                    float theta, int32_t W, uint64_t seed, uint64_t offset,
+                                    int32_t* sampled, const fly_verify_out* out, void* workspace,
+                                    size_t workspace_bytes, fly_stream stream);
+
+/*
  * The sequences of a multi-round decode (Algorithm 1: y, and the counters s, t).
  * Row b of ctx holds y of sequence b: the prompt followed by everything emitted
  * so far; ctx_len[b] tokens are valid.  The last token of a row is y_{-1}: it
@@ -299,6 +324,17 @@ fly_status fly_lmhead_entropy_argmax(const void* hidden, const void* w_lm, const
                                      int32_t M, int32_t d, int32_t V, int32_t dtype,
                                      int32_t* argmax, float* p_top1, float* h_norm, float* lse,
                                      void* workspace, size_t workspace_bytes, fly_stream stream);
+
+/*
+ * The same with one token per row drawn from softmax(row_scale[m] * logits[m])
+ * as well (see fly_verify_block_sampled for the construction; row m of this
+ * call is row m of the counter).  sampled [device] int32 [M].  Same workspace.
+ */
+fly_status fly_lmhead_entropy_sample(const void* hidden, const void* w_lm, const float* row_scale,
+                                     int32_t M, int32_t d, int32_t V, int32_t dtype, uint64_t seed,
+                                     uint64_t offset, int32_t* sampled, int32_t* argmax, float* p_top1,
+                                     float* h_norm, float* lse, void* workspace, size_t workspace_bytes,
+                                     fly_stream stream);
 
 /*
  * FLy's loose acceptance rule (Eqs. 2-11; Algorithm 1 steps 3-4).

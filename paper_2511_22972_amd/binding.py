@@ -25,7 +25,7 @@ EXPORTS = [
     "fly_lmhead_entropy_argmax", "fly_accept", "fly_attention", "fly_gateup_swiglu", "fly_proj_partial",
     "fly_pld_draft", "fly_decode_workspace_bytes", "fly_decode_rounds",
     "fly_model_draft_workspace_bytes", "fly_model_draft", "fly_decode_model_workspace_bytes",
-    "fly_decode_rounds_model",
+    "fly_decode_rounds_model", "fly_verify_block_sampled", "fly_lmhead_entropy_sample",
 ]
 
 
@@ -90,6 +90,15 @@ def _load() -> C.CDLL:
                                      C.POINTER(fly_kv_cache), C.c_void_p, C.c_void_p, C.c_int32,
                                      C.c_int32, C.c_float, C.c_int32, C.POINTER(fly_verify_out),
                                      C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.fly_verify_block_sampled.argtypes = [C.POINTER(fly_model_desc), C.POINTER(fly_weights),
+                                             C.POINTER(fly_kv_cache), C.c_void_p, C.c_void_p, C.c_int32,
+                                             C.c_int32, C.c_float, C.c_int32, C.c_uint64, C.c_uint64,
+                                             C.c_void_p, C.POINTER(fly_verify_out), C.c_void_p,
+                                             C.c_size_t, C.c_void_p]
+    lib.fly_lmhead_entropy_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                              C.c_int32, C.c_int32, C.c_uint64, C.c_uint64, C.c_void_p,
+                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                              C.c_size_t, C.c_void_p]
     lib.fly_decoder_layers.argtypes = [C.POINTER(fly_model_desc), C.POINTER(fly_weights),
                                        C.POINTER(fly_kv_cache), C.c_void_p, C.c_int32, C.c_int32,
                                        C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -217,6 +226,19 @@ def fly_lmhead_entropy_argmax(hidden: torch.Tensor, w_lm_packed: torch.Tensor,
            "fly_lmhead_entropy_argmax")
 
 
+def fly_lmhead_entropy_sample(hidden: torch.Tensor, w_lm_packed: torch.Tensor,
+                              row_scale: Optional[torch.Tensor], V: int, seed: int, offset: int,
+                              sampled: torch.Tensor, argmax: torch.Tensor, p_top1: torch.Tensor,
+                              h_norm: torch.Tensor, lse: Optional[torch.Tensor],
+                              workspace: torch.Tensor) -> None:
+    M, d = hidden.shape
+    _check(lib.fly_lmhead_entropy_sample(_ptr(hidden), _ptr(w_lm_packed), _ptr(row_scale), M, d, V,
+                                         dtype_code(hidden.dtype), seed, offset, _ptr(sampled),
+                                         _ptr(argmax), _ptr(p_top1), _ptr(h_norm), _ptr(lse),
+                                         _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                         _stream()), "fly_lmhead_entropy_sample")
+
+
 # ---------------------------------------------------------------------------
 # Holders of device memory (allocation and layout plumbing, no arithmetic)
 # ---------------------------------------------------------------------------
@@ -340,6 +362,19 @@ def fly_verify_block(model: PackedModel, kv: KVCache, tokens: torch.Tensor,
                                 _ptr(tokens), _ptr(row_scale), B, R - 1, theta, W, C.byref(outs),
                                 _ptr(workspace), workspace.numel() * workspace.element_size(),
                                 _stream()), "fly_verify_block")
+
+
+def fly_verify_block_sampled(model: PackedModel, kv: KVCache, tokens: torch.Tensor,
+                             row_scale: Optional[torch.Tensor], theta: float, W: int, seed: int,
+                             offset: int, sampled: torch.Tensor, out: VerifyOutputs,
+                             workspace: torch.Tensor) -> None:
+    B, R = tokens.shape
+    kvs, outs = kv.struct(), out.struct()
+    _check(lib.fly_verify_block_sampled(C.byref(model.desc), C.byref(model.weights_c), C.byref(kvs),
+                                        _ptr(tokens), _ptr(row_scale), B, R - 1, theta, W, seed, offset,
+                                        _ptr(sampled), C.byref(outs), _ptr(workspace),
+                                        workspace.numel() * workspace.element_size(), _stream()),
+           "fly_verify_block_sampled")
 
 
 class Sequences:

@@ -164,9 +164,11 @@ struct Plans {
   int lm_parts;
 };
 
+// Per (row, part): four floats of softmax statistics, then (behind all of them) two floats of the
+// sampled-token pick.
 size_t lmhead_partial_floats(int M, int V, int dtype, const GemmPlan& lm) {
   int parts = dtype == FLY_BF16 ? gemm_bf16_lmhead_parts(V, lm) : gemm_f32_lmhead_parts(V);
-  return (size_t)M * parts * 4;
+  return (size_t)M * parts * 6;
 }
 
 fly_status check_desc(const fly_model_desc* desc) {
@@ -242,7 +244,7 @@ void carve(const fly_model_desc* desc, int B, int K, const Plans& pl, void* base
                                                                    desc->head_dim, pl.attn)
                                       : 0;
   ws->attn = (float*)take(af * 4);
-  ws->lm_partial = (float*)take((size_t)M * pl.lm_parts * 16);
+  ws->lm_partial = (float*)take((size_t)M * pl.lm_parts * 24);  // statistics, then picks
   ws->bytes = off;
 }
 
@@ -291,21 +293,47 @@ fly_status check_weights(const fly_model_desc* desc, const fly_weights* w, int l
   return FLY_OK;
 }
 
-// One GEMM of the layer in either dtype; bf16 may leave split-K partials.
-fly_status run_gemm(int dtype, const void* X, const void* W, void* out, const float* row_scale, int M,
-                    int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st) {
-  if (dtype == FLY_BF16)
-    HIP_TRY(launch_gemm_bf16((const bf16_t*)X, (const bf16_t*)W, out, row_scale, M, N, Kd, plan, epi, st));
-  else
-    HIP_TRY(launch_gemm_f32((const float*)X, (const float*)W, out, row_scale, M, N, Kd, epi, st));
-  return FLY_OK;
-}
-
 #define FLY_TRY(expr)               \
   do {                              \
     fly_status _s = (expr);         \
     if (_s != FLY_OK) return _s;    \
   } while (0)
+
+// One GEMM of the layer in either dtype; bf16 may leave split-K partials.
+fly_status run_gemm(int dtype, const void* X, const void* W, void* out, const float* row_scale, int M,
+                    int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st,
+                    const LmSample& smp = LmSample{}) {
+  if (dtype == FLY_BF16)
+    HIP_TRY(launch_gemm_bf16((const bf16_t*)X, (const bf16_t*)W, out, row_scale, M, N, Kd, plan, epi, st, smp));
+  else
+    HIP_TRY(launch_gemm_f32((const float*)X, (const float*)W, out, row_scale, M, N, Kd, epi, st, smp));
+  return FLY_OK;
+}
+
+// A request to draw the row's token as well (seed, offset, where the drawn tokens go).
+struct SampleRequest {
+  uint64_t seed, offset;
+  int32_t* sampled;  // [M]
+};
+// LM head with fused statistics on `partial` (M * parts * 6 floats): logits stay in registers.
+fly_status run_lmhead(int dtype, const void* xn, const void* w_lm, float* partial, const float* row_scale,
+                      int M, int V, int d, const GemmPlan& lm, int parts, int32_t* argmax, float* p_top1,
+                      float* h_norm, float* lse, const SampleRequest* sr, hipStream_t st) {
+  if (sr == nullptr) {
+    FLY_TRY(run_gemm(dtype, xn, w_lm, partial, row_scale, M, V, d, lm, EPI_LMHEAD, st));
+    HIP_TRY(launch_lmhead_combine(partial, parts, M, V, argmax, p_top1, h_norm, lse, st));
+    return FLY_OK;
+  }
+  LmSample smp;
+  smp.pick = partial + (size_t)M * parts * 4;
+  smp.key0 = (uint32_t)sr->seed;
+  smp.key1 = (uint32_t)(sr->seed >> 32);
+  smp.ctr2 = (uint32_t)sr->offset;
+  smp.ctr3 = (uint32_t)(sr->offset >> 32);
+  FLY_TRY(run_gemm(dtype, xn, w_lm, partial, row_scale, M, V, d, lm, EPI_LMSAMPLE, st, smp));
+  HIP_TRY(launch_lmhead_combine(partial, parts, M, V, argmax, p_top1, h_norm, lse, st, smp.pick, sr->sampled));
+  return FLY_OK;
+}
 
 // Layers [l0, l1) on the residual stream ws.x; ws.xn must hold
 // rmsnorm(x) * g_attn[l0] on entry and holds rmsnorm(x) * next_gain on exit
@@ -350,7 +378,7 @@ fly_status run_layers(const fly_model_desc* desc, const fly_weights* w, const fl
 fly_status run_forward(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
                        const int32_t* tokens, const float* row_scale, int B, int K, int32_t* argmax,
                        float* p_top1, float* h_norm, float* lse, float* hidden_out, const Workspace& ws,
-                       const Plans& pl, hipStream_t st) {
+                       const Plans& pl, hipStream_t st, const SampleRequest* sr = nullptr) {
   const int M = B * (K + 1), d = desc->d, dt = desc->dtype;
   HIP_TRY(launch_rope_table(kv->kv_len, ws.rope, B, K, desc->head_dim, desc->rope_theta, st));
   HIP_TRY(launch_embed(tokens, w->embed, dt, ws.x, M, d, desc->vocab, st));
@@ -359,20 +387,20 @@ fly_status run_forward(const fly_model_desc* desc, const fly_weights* w, const f
   FLY_TRY(run_layers(desc, w, kv, ws, pl, 0, desc->n_layers, B, K, st));
   if (hidden_out)
     HIP_TRY(hipMemcpyAsync(hidden_out, ws.x, (size_t)M * d * 4, hipMemcpyDeviceToDevice, st));
-  // LM head with fused statistics: logits stay in registers
-  FLY_TRY(run_gemm(dt, ws.xn, w->w_lm, ws.lm_partial, row_scale, M, desc->vocab, d, pl.lm, EPI_LMHEAD, st));
-  HIP_TRY(launch_lmhead_combine(ws.lm_partial, pl.lm_parts, M, desc->vocab, argmax, p_top1, h_norm, lse, st));
-  return FLY_OK;
+  return run_lmhead(dt, ws.xn, w->w_lm, ws.lm_partial, row_scale, M, desc->vocab, d, pl.lm, pl.lm_parts,
+                    argmax, p_top1, h_norm, lse, sr, st);
 }
 
-// The step itself: forward, then the acceptance rule on (draft, argmax, h).
+// The step itself: forward, then the acceptance rule on (draft, target token, h).  The target's
+// token is the argmax (Eq. 1) or, with a sample request, the token drawn from the same softmax.
 fly_status run_verify(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
                       const int32_t* tokens, const float* row_scale, int B, int K, float theta, int W,
-                      const fly_verify_out* out, const Workspace& ws, const Plans& pl, hipStream_t st) {
+                      const fly_verify_out* out, const Workspace& ws, const Plans& pl, hipStream_t st,
+                      const SampleRequest* sr = nullptr) {
   FLY_TRY(run_forward(desc, w, kv, tokens, row_scale, B, K, out->argmax, out->p_top1, out->h_norm, out->lse,
-                      out->hidden_out, ws, pl, st));
-  HIP_TRY(launch_accept(tokens + 1, K + 1, out->argmax, out->h_norm, kv->kv_len, B, K, theta, W,
-                        out->accept_len, out->next_token, out->n_loose, out->kv_len_out, st));
+                      out->hidden_out, ws, pl, st, sr));
+  HIP_TRY(launch_accept(tokens + 1, K + 1, sr ? sr->sampled : out->argmax, out->h_norm, kv->kv_len, B, K,
+                        theta, W, out->accept_len, out->next_token, out->n_loose, out->kv_len_out, st));
   return FLY_OK;
 }
 
@@ -582,21 +610,38 @@ fly_status fly_lmhead_workspace_bytes(int32_t M, int32_t d, int32_t V, int32_t d
   return FLY_OK;
 }
 
-fly_status fly_lmhead_entropy_argmax(const void* hidden, const void* w_lm, const float* row_scale,
-                                     int32_t M, int32_t d, int32_t V, int32_t dtype, int32_t* argmax,
-                                     float* p_top1, float* h_norm, float* lse, void* workspace,
-                                     size_t workspace_bytes, fly_stream stream) {
+static fly_status lmhead_entry(const void* hidden, const void* w_lm, const float* row_scale, int32_t M,
+                               int32_t d, int32_t V, int32_t dtype, int32_t* argmax, float* p_top1,
+                               float* h_norm, float* lse, const SampleRequest* sr, void* workspace,
+                               size_t workspace_bytes, fly_stream stream) {
   if (!hidden || !w_lm || !argmax || !p_top1 || !h_norm) return FLY_ERR_NULL_POINTER;
+  if (sr && !sr->sampled) return FLY_ERR_NULL_POINTER;
   size_t need = 0;
   FLY_TRY(fly_lmhead_workspace_bytes(M, d, V, dtype, &need));
   if (!workspace || workspace_bytes < need) return FLY_ERR_WORKSPACE;
   if (!aligned16(hidden) || !aligned16(w_lm) || !aligned16(workspace)) return FLY_ERR_ALIGNMENT;
-  hipStream_t st = (hipStream_t)stream;
   GemmPlan lm = dtype == FLY_BF16 ? plan_gemm(M, V, d, false, false) : GemmPlan{1, 1, 1, 1};
   int parts = dtype == FLY_BF16 ? gemm_bf16_lmhead_parts(V, lm) : gemm_f32_lmhead_parts(V);
-  FLY_TRY(run_gemm(dtype, hidden, w_lm, workspace, row_scale, M, V, d, lm, EPI_LMHEAD, st));
-  HIP_TRY(launch_lmhead_combine((const float*)workspace, parts, M, V, argmax, p_top1, h_norm, lse, st));
-  return FLY_OK;
+  return run_lmhead(dtype, hidden, w_lm, (float*)workspace, row_scale, M, V, d, lm, parts, argmax, p_top1,
+                    h_norm, lse, sr, (hipStream_t)stream);
+}
+
+fly_status fly_lmhead_entropy_argmax(const void* hidden, const void* w_lm, const float* row_scale,
+                                     int32_t M, int32_t d, int32_t V, int32_t dtype, int32_t* argmax,
+                                     float* p_top1, float* h_norm, float* lse, void* workspace,
+                                     size_t workspace_bytes, fly_stream stream) {
+  return lmhead_entry(hidden, w_lm, row_scale, M, d, V, dtype, argmax, p_top1, h_norm, lse, nullptr,
+                      workspace, workspace_bytes, stream);
+}
+
+fly_status fly_lmhead_entropy_sample(const void* hidden, const void* w_lm, const float* row_scale,
+                                     int32_t M, int32_t d, int32_t V, int32_t dtype, uint64_t seed,
+                                     uint64_t offset, int32_t* sampled, int32_t* argmax, float* p_top1,
+                                     float* h_norm, float* lse, void* workspace, size_t workspace_bytes,
+                                     fly_stream stream) {
+  SampleRequest sr{seed, offset, sampled};
+  return lmhead_entry(hidden, w_lm, row_scale, M, d, V, dtype, argmax, p_top1, h_norm, lse, &sr, workspace,
+                      workspace_bytes, stream);
 }
 
 fly_status fly_accept(const int32_t* draft, const int32_t* tgt_argmax, const float* h_norm, int32_t B,
@@ -692,11 +737,12 @@ fly_status fly_gateup_swiglu(const void* xn, const void* w_gateup, void* a, int3
   return run_gemm(dtype, xn, w_gateup, a, nullptr, M, 2 * F, d, plan, EPI_SWIGLU, (hipStream_t)stream);
 }
 
-fly_status fly_verify_block(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
-                            const int32_t* tokens, const float* row_scale, int32_t B, int32_t K,
-                            float theta, int32_t W, const fly_verify_out* out, void* workspace,
-                            size_t workspace_bytes, fly_stream stream) {
+static fly_status verify_entry(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                               const int32_t* tokens, const float* row_scale, int32_t B, int32_t K,
+                               float theta, int32_t W, const fly_verify_out* out, const SampleRequest* sr,
+                               void* workspace, size_t workspace_bytes, fly_stream stream) {
   FLY_TRY(check_desc(desc));
+  if (sr && !sr->sampled) return FLY_ERR_NULL_POINTER;
   FLY_TRY(check_block(B, K));
   if (W < 0) return FLY_ERR_WINDOW;
   if (theta != theta) return FLY_ERR_THETA;
@@ -713,7 +759,25 @@ fly_status fly_verify_block(const fly_model_desc* desc, const fly_weights* w, co
   if (!workspace || workspace_bytes < ws.bytes) return FLY_ERR_WORKSPACE;
   if (!aligned16(workspace)) return FLY_ERR_ALIGNMENT;
   carve(desc, B, K, pl, workspace, &ws);
-  return run_verify(desc, w, kv, tokens, row_scale, B, K, theta, W, out, ws, pl, (hipStream_t)stream);
+  return run_verify(desc, w, kv, tokens, row_scale, B, K, theta, W, out, ws, pl, (hipStream_t)stream, sr);
+}
+
+fly_status fly_verify_block(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                            const int32_t* tokens, const float* row_scale, int32_t B, int32_t K,
+                            float theta, int32_t W, const fly_verify_out* out, void* workspace,
+                            size_t workspace_bytes, fly_stream stream) {
+  return verify_entry(desc, w, kv, tokens, row_scale, B, K, theta, W, out, nullptr, workspace,
+                      workspace_bytes, stream);
+}
+
+fly_status fly_verify_block_sampled(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                                    const int32_t* tokens, const float* row_scale, int32_t B, int32_t K,
+                                    float theta, int32_t W, uint64_t seed, uint64_t offset,
+                                    int32_t* sampled, const fly_verify_out* out, void* workspace,
+                                    size_t workspace_bytes, fly_stream stream) {
+  SampleRequest sr{seed, offset, sampled};
+  return verify_entry(desc, w, kv, tokens, row_scale, B, K, theta, W, out, &sr, workspace, workspace_bytes,
+                      stream);
 }
 
 fly_status fly_pld_draft(const int32_t* ctx, const int32_t* ctx_len, int32_t ctx_capacity, int32_t B,

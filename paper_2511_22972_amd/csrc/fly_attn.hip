@@ -42,7 +42,6 @@
 // row are two runs of eight consecutive keys, i.e. exactly the operand order
 // of the P V product, whose V^T fragments are then whole 16-byte pieces.
 #define ATT_KPERM(i) (((i) & 0x13) | (((i) & 4) << 1) | (((i) & 8) >> 1))
-typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 // LDS-direct load: every lane gives its own global address of 16 bytes, the wave's
 // 1 KiB lands at lds_base + 16 * lane (lds_base wave-uniform, passed in M0).

@@ -84,6 +84,97 @@ __device__ __forceinline__ RowStat stat_shfl_xor(const RowStat& a, int o) {
   return r;
 }
 
+// ---- drawing a token from the softmax of the scaled logits -----------------
+// The paper reports temperature-1 results (Tables 1-2) and states its rule with
+// the argmax only (Eqs. 1-2); here the drawn token takes the argmax's place.
+// Gumbel-max construction: argmax_v (l_v + G_v) with independent standard Gumbel
+// variates G_v = -ln(-ln u_v) is distributed as softmax(l), and it needs the
+// logits once, in any order, like the other row statistics.  u_v comes from
+// Philox4x32 with ten rounds (Salmon et al., SC 2011): word v % 4 of the block
+// with counter (v / 4, row, offset low, offset high) and key (seed low, seed
+// high); u = (top 23 bits + 1/2) / 2^23 lies strictly inside (0, 1).
+struct LmSample {
+  float* pick;           // [M][nparts][2]: largest perturbed logit and its column (as int bits)
+  uint32_t key0, key1;   // seed
+  uint32_t ctr2, ctr3;   // the caller's 64-bit offset: tells calls with one seed apart
+};
+struct RowPick {
+  float z;
+  int32_t idx;
+};
+__device__ __forceinline__ RowPick pick_empty() { return RowPick{-INFINITY, 0x7fffffff}; }
+__device__ __forceinline__ RowPick pick_merge(const RowPick& a, const RowPick& b) {
+  return (a.z > b.z) ? a : (b.z > a.z) ? b : (a.idx < b.idx ? a : b);
+}
+__device__ __forceinline__ RowPick pick_shfl_xor(const RowPick& a, int o) {
+  return RowPick{__shfl_xor(a.z, o, FLY_WAVE), __shfl_xor(a.idx, o, FLY_WAVE)};
+}
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4]) {
+  // kept as a loop: the epilogues call this once per four logits of up to 48 register tiles, and
+  // unrolled ten-fold those bodies outgrow what the compiler is willing to unroll around them
+#pragma unroll 1
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0;
+    c1 = lo1;
+    c2 = n2;
+    c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0;
+  out[1] = c1;
+  out[2] = c2;
+  out[3] = c3;
+}
+__device__ __forceinline__ float gumbel_from_bits(uint32_t bits) {
+  const float u = ((float)(bits >> 9) + 0.5f) * 1.1920928955078125e-07f;  // 2^-23; exact in fp32
+  // the inner logarithm must be accurate relative to its result also for u next to 1 (the largest
+  // variates, the ones that win); the outer one only to ~1e-6 absolute
+  return -__logf(-logf(u));
+}
+// Folds the four scaled logits of columns col0 .. col0+3 (col0 a multiple of 4) of row `row`.
+__device__ __forceinline__ void pick_update4(RowPick& p, float v0, float v1, float v2, float v3, int col0,
+                                             int row, const LmSample& smp) {
+  uint32_t x[4];
+  philox4x32_10((uint32_t)col0 >> 2, (uint32_t)row, smp.ctr2, smp.ctr3, smp.key0, smp.key1, x);
+  const float v[4] = {v0, v1, v2, v3};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float z = v[e] + gumbel_from_bits(x[e]);
+    if (z > p.z || (z == p.z && col0 + e < p.idx)) {
+      p.z = z;
+      p.idx = col0 + e;
+    }
+  }
+}
+// The sixteen logits a lane holds of one 32 x 32 matrix-core tile: columns
+// n0 + 8 (r/4) + 4 hi + r%4 of one row, i.e. four aligned groups of four.
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+__device__ __forceinline__ void pick_update_tile32(RowPick& p, const f32x16& v, float sc, int n0, int hi,
+                                                   int N, int row, const LmSample& smp) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int col0 = n0 + 8 * q + 4 * hi;
+    if (col0 < N)  // N is a multiple of 16: a group of four is inside or outside as a whole
+      pick_update4(p, v[4 * q] * sc, v[4 * q + 1] * sc, v[4 * q + 2] * sc, v[4 * q + 3] * sc, col0, row, smp);
+  }
+}
+// One column (the fp32 kernel holds one logit per lane).
+__device__ __forceinline__ RowPick pick_one(float v, int col, int row, const LmSample& smp) {
+  uint32_t x[4];
+  philox4x32_10((uint32_t)col >> 2, (uint32_t)row, smp.ctr2, smp.ctr3, smp.key0, smp.key1, x);
+  const uint32_t bits = (col & 3) == 0 ? x[0] : (col & 3) == 1 ? x[1] : (col & 3) == 2 ? x[2] : x[3];
+  return RowPick{v + gumbel_from_bits(bits), col};
+}
+__device__ __forceinline__ void pick_store(const LmSample& smp, int64_t slot, const RowPick& p) {
+  smp.pick[2 * slot] = p.z;
+  smp.pick[2 * slot + 1] = __int_as_float(p.idx);
+}
+
 // LDS-direct load: every lane gives its own global address of 16 bytes, the wave's
 // 1 KiB lands at lds_base + 16 * lane (lds_base wave-uniform, passed in M0).  It
 // is issued from inline assembly on purpose: the compiler's automatic wait
@@ -132,7 +223,7 @@ struct GemmPlan {
                // (5, 6, 8); takes precedence over the other fields except splits
 };
 
-enum GemmEpilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_LMHEAD = 2 };
+enum GemmEpilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_LMHEAD = 2, EPI_LMSAMPLE = 3 };
 
 hipError_t launch_pack_weight(const void* src, int64_t k_in, int64_t n_src, int dtype, void* dst,
                               int64_t n_dst, int64_t tile_offset, int64_t tile_stride,
@@ -143,16 +234,21 @@ hipError_t launch_pack_weight(const void* src, int64_t k_in, int64_t n_src, int 
 //   EPI_SWIGLU : out = bf16 a[M][N/2], a = silu(gate)*up (splits must be 1)
 //   EPI_LMHEAD : out = RowStat-like float4 partial[M][nparts] (splits must be 1),
 //                logits multiplied by row_scale[m] first
+//   EPI_LMSAMPLE: EPI_LMHEAD, and smp.pick[M][nparts] receives the largest Gumbel-perturbed
+//                logit of each part and its column
 hipError_t launch_gemm_bf16(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale,
-                            int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st);
+                            int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st,
+                            const LmSample& smp = LmSample{});
 int gemm_bf16_lmhead_parts(int N, const GemmPlan& plan);
 // LDS-tiled variant for large M (called through launch_gemm_bf16 when plan.tiled != 0).
 hipError_t launch_gemm_bf16_tiled(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale,
-                                  int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st);
+                                  int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st,
+                                  const LmSample& smp = LmSample{});
 int gemm_bf16_tiled_lmhead_parts(int N, int tiled);
 // Weight-streaming variant for 129..256 rows (called through launch_gemm_bf16 when plan.wide != 0).
 hipError_t launch_gemm_bf16_wide(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale, int M,
-                                 int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st);
+                                 int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st,
+                                 const LmSample& smp = LmSample{});
 int gemm_bf16_wide_lmhead_parts(int N);
 int gemm_bf16_wide_cols();  // columns one workgroup covers
 int gemm_bf16_tiled_rows(int tiled);
@@ -160,7 +256,7 @@ int gemm_bf16_tiled_cols(int tiled);
 
 // fp32 GEMM (weights row-major [Kd,N]) with the same epilogues; no split-K.
 hipError_t launch_gemm_f32(const float* X, const float* W, void* out, const float* row_scale, int M,
-                           int N, int Kd, int epi, hipStream_t st);
+                           int N, int Kd, int epi, hipStream_t st, const LmSample& smp = LmSample{});
 int gemm_f32_lmhead_parts(int N);
 
 hipError_t launch_embed(const int32_t* tokens, const void* embed, int dtype, float* x, int M, int d,
@@ -176,8 +272,10 @@ hipError_t launch_rope_table(const int32_t* kv_len, float* table, int B, int K, 
 hipError_t launch_qkv_epilogue(const float* partial, int splits, const float* rope, void* q,
                                void* kcache, void* vcache, const int32_t* kv_len, int dtype, int B,
                                int K, int Hq, int Hkv, int hd, int capacity, hipStream_t st);
+// pick / sampled: the per-part picks of EPI_LMSAMPLE and the drawn token per row, or both NULL.
 hipError_t launch_lmhead_combine(const float* partial, int nparts, int M, int V, int32_t* argmax,
-                                 float* p_top1, float* h_norm, float* lse, hipStream_t st);
+                                 float* p_top1, float* h_norm, float* lse, hipStream_t st,
+                                 const float* pick = nullptr, int32_t* sampled = nullptr);
 hipError_t launch_accept(const int32_t* draft, int draft_stride, const int32_t* tgt,
                          const float* h_norm, const int32_t* kv_len, int B, int K, float theta,
                          int W, int32_t* accept_len, int32_t* next_token, int32_t* n_loose,

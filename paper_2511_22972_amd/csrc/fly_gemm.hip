@@ -102,7 +102,7 @@ template <int MT, int NT, int EPI, int KS, int RING>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     const bf16_t* __restrict__ X, const u32x4* __restrict__ Wp, void* __restrict__ out,
     const float* __restrict__ row_scale, int M, int N, int Kd, int chunks_per_split, int nblocks,
-    int mblocks) {
+    int mblocks, LmSample smp) {
   // Workgroup -> (column block, row block).  Workgroups are dealt to the eight
   // XCDs (each with its own L2) round-robin by linear id.  When the activations
   // need several row blocks, the row blocks of one column block re-read the same
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
         }
       }
     }
-  } else {  // EPI_LMHEAD: per-wave softmax statistics of this wave's columns
+  } else {  // EPI_LMHEAD / EPI_LMSAMPLE: per-wave softmax statistics of this wave's columns
     f32x4* o = (f32x4*)out;
     const int nparts = nblocks * 4;
     const int part = nblock * 4 + wave;
@@ -347,6 +347,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
         w.w = __int_as_float(st.idx);
         o[(int64_t)m * nparts + part] = w;
       }
+      if constexpr (EPI == EPI_LMSAMPLE) {
+        // the drawn token: largest Gumbel-perturbed logit of this wave's columns
+        RowPick pk = pick_empty();
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+          if (tile_ok[j])
+            pick_update4(pk, v[j][0], v[j][1], v[j][2], v[j][3], (tn0 + j) * 16 + 4 * g, m, smp);
+        pk = pick_merge(pk, pick_shfl_xor(pk, 16));
+        pk = pick_merge(pk, pick_shfl_xor(pk, 32));
+        if (g == 0 && m < M) pick_store(smp, (int64_t)m * nparts + part, pk);
+      }
     }
   }
 }
@@ -354,7 +365,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
 template <int MT, int NT>
 static hipError_t launch_gemm_mt_nt(const bf16_t* X, const bf16_t* Wp, void* out,
                                     const float* row_scale, int M, int N, int Kd,
-                                    const GemmPlan& plan, int epi, hipStream_t st) {
+                                    const GemmPlan& plan, int epi, hipStream_t st, const LmSample& smp) {
   constexpr int KS = MT >= 9 ? 2 : 4;
   constexpr int RING = MT >= 9 ? 4 : 3;  // the same bytes in flight with half-size chunks
   int ntiles = N / 16;
@@ -365,17 +376,20 @@ static hipError_t launch_gemm_mt_nt(const bf16_t* X, const bf16_t* Wp, void* out
   const u32x4* W4 = (const u32x4*)Wp;
   if (epi == EPI_PARTIAL) {
     hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_PARTIAL, KS, RING>), grid, block, 0, st, X, W4, out,
-                       row_scale, M, N, Kd, cps, nblocks, plan.mblocks);
+                       row_scale, M, N, Kd, cps, nblocks, plan.mblocks, smp);
   } else if (epi == EPI_SWIGLU) {
     if constexpr (NT >= 2) {
       hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_SWIGLU, KS, RING>), grid, block, 0, st, X, W4, out,
-                         row_scale, M, N, Kd, cps, nblocks, plan.mblocks);
+                         row_scale, M, N, Kd, cps, nblocks, plan.mblocks, smp);
     } else {
       return hipErrorInvalidValue;
     }
-  } else {
+  } else if (epi == EPI_LMHEAD) {
     hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_LMHEAD, KS, RING>), grid, block, 0, st, X, W4, out,
-                       row_scale, M, N, Kd, cps, nblocks, plan.mblocks);
+                       row_scale, M, N, Kd, cps, nblocks, plan.mblocks, smp);
+  } else {
+    hipLaunchKernelGGL((gemm_bf16_kernel<MT, NT, EPI_LMSAMPLE, KS, RING>), grid, block, 0, st, X, W4, out,
+                       row_scale, M, N, Kd, cps, nblocks, plan.mblocks, smp);
   }
   return hipGetLastError();
 }
@@ -383,19 +397,22 @@ static hipError_t launch_gemm_mt_nt(const bf16_t* X, const bf16_t* Wp, void* out
 template <int MT>
 static hipError_t launch_gemm_mt(const bf16_t* X, const bf16_t* Wp, void* out,
                                  const float* row_scale, int M, int N, int Kd, const GemmPlan& plan,
-                                 int epi, hipStream_t st) {
+                                 int epi, hipStream_t st, const LmSample& smp) {
   switch (plan.nt) {
-    case 1: return launch_gemm_mt_nt<MT, 1>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 2: return launch_gemm_mt_nt<MT, 2>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 4: return launch_gemm_mt_nt<MT, 4>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+    case 1: return launch_gemm_mt_nt<MT, 1>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 2: return launch_gemm_mt_nt<MT, 2>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 4: return launch_gemm_mt_nt<MT, 4>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
   }
   return hipErrorInvalidValue;
 }
 
 hipError_t launch_gemm_bf16(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale,
-                            int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st) {
-  if (plan.wide) return launch_gemm_bf16_wide(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-  if (plan.tiled) return launch_gemm_bf16_tiled(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+                            int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st,
+                            const LmSample& smp) {
+  if (epi < EPI_PARTIAL || epi > EPI_LMSAMPLE) return hipErrorInvalidValue;
+  if (epi == EPI_LMSAMPLE && smp.pick == nullptr) return hipErrorInvalidValue;
+  if (plan.wide) return launch_gemm_bf16_wide(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+  if (plan.tiled) return launch_gemm_bf16_tiled(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
   // Host-side shape checks: the kernel assumes whole 16-column tiles and whole
   // 32-row k-steps, and that the row blocks cover M.
   if (N % 16 != 0 || Kd % 32 != 0 || M < 1) return hipErrorInvalidValue;
@@ -403,11 +420,11 @@ hipError_t launch_gemm_bf16(const bf16_t* X, const bf16_t* Wp, void* out, const 
   if (epi != EPI_PARTIAL && plan.splits != 1) return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU && (N % 32 != 0)) return hipErrorInvalidValue;
   switch (plan.mt) {
-    case 1: return launch_gemm_mt<1>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 2: return launch_gemm_mt<2>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 3: return launch_gemm_mt<3>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 5: return launch_gemm_mt<5>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 9: return launch_gemm_mt<9>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+    case 1: return launch_gemm_mt<1>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 2: return launch_gemm_mt<2>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 3: return launch_gemm_mt<3>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 5: return launch_gemm_mt<5>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 9: return launch_gemm_mt<9>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
   }
   return hipErrorInvalidValue;
 }
@@ -434,7 +451,7 @@ __global__ __launch_bounds__(64 * F32_KSL) void gemm_f32_kernel(const float* __r
                                                                 const float* __restrict__ W,
                                                                 void* __restrict__ out,
                                                                 const float* __restrict__ row_scale,
-                                                                int M, int N, int Kd) {
+                                                                int M, int N, int Kd, LmSample smp) {
   __shared__ float red[F32_KSL][F32_MB][64];
   const int c = threadIdx.x & 63, slice = threadIdx.x >> 6;
   const int n = blockIdx.x * 64 + c;
@@ -505,20 +522,30 @@ __global__ __launch_bounds__(64 * F32_KSL) void gemm_f32_kernel(const float* __r
       w.w = __int_as_float(st.idx);
       o[(int64_t)m * nparts + blockIdx.x] = w;
     }
+    if constexpr (EPI == EPI_LMSAMPLE) {
+      RowPick pk = n < N ? pick_one(red[0][r][c] * sc, n, m, smp) : pick_empty();
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) pk = pick_merge(pk, pick_shfl_xor(pk, off));
+      if (c == 0 && m < M) pick_store(smp, (int64_t)m * nparts + blockIdx.x, pk);
+    }
   }
 }
 
 hipError_t launch_gemm_f32(const float* X, const float* W, void* out, const float* row_scale, int M,
-                           int N, int Kd, int epi, hipStream_t st) {
+                           int N, int Kd, int epi, hipStream_t st, const LmSample& smp) {
   if (N % 16 != 0 || M < 1 || Kd < 1) return hipErrorInvalidValue;
+  if (epi < EPI_PARTIAL || epi > EPI_LMSAMPLE) return hipErrorInvalidValue;
+  if (epi == EPI_LMSAMPLE && smp.pick == nullptr) return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU && N % 32 != 0) return hipErrorInvalidValue;
   dim3 grid((N + 63) / 64, (M + F32_MB - 1) / F32_MB), block(64 * F32_KSL);
   if (epi == EPI_PARTIAL)
-    hipLaunchKernelGGL((gemm_f32_kernel<EPI_PARTIAL>), grid, block, 0, st, X, W, out, row_scale, M, N, Kd);
+    hipLaunchKernelGGL((gemm_f32_kernel<EPI_PARTIAL>), grid, block, 0, st, X, W, out, row_scale, M, N, Kd, smp);
   else if (epi == EPI_SWIGLU)
-    hipLaunchKernelGGL((gemm_f32_kernel<EPI_SWIGLU>), grid, block, 0, st, X, W, out, row_scale, M, N, Kd);
+    hipLaunchKernelGGL((gemm_f32_kernel<EPI_SWIGLU>), grid, block, 0, st, X, W, out, row_scale, M, N, Kd, smp);
+  else if (epi == EPI_LMHEAD)
+    hipLaunchKernelGGL((gemm_f32_kernel<EPI_LMHEAD>), grid, block, 0, st, X, W, out, row_scale, M, N, Kd, smp);
   else
-    hipLaunchKernelGGL((gemm_f32_kernel<EPI_LMHEAD>), grid, block, 0, st, X, W, out, row_scale, M, N, Kd);
+    hipLaunchKernelGGL((gemm_f32_kernel<EPI_LMSAMPLE>), grid, block, 0, st, X, W, out, row_scale, M, N, Kd, smp);
   return hipGetLastError();
 }
 

@@ -13,7 +13,6 @@
 // barrier per k-step.
 #include "fly_common.h"
 
-typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 namespace {
 
@@ -98,7 +97,7 @@ template <int WGN, int WGM, int WM, int EPI, int NS>
 __global__ __launch_bounds__(WGN* WGM * 64) void gemm_bf16_tiled_kernel(
     const bf16_t* __restrict__ X, const u32x4* __restrict__ Wp, void* __restrict__ out,
     const float* __restrict__ row_scale, int M, int N, int Kd, int kt_per_split, int nblocks,
-    int mblocks) {
+    int mblocks, LmSample smp) {
   constexpr int NW = WGN * WGM;                // waves
   constexpr int WLOADS = 8 * WGN / NW;         // LDS-direct loads per wave and stage: weights
   constexpr int XLOADS = 2 * WM * WGM / NW;    //                                      activations
@@ -232,7 +231,7 @@ __global__ __launch_bounds__(WGN* WGM * 64) void gemm_bf16_tiled_kernel(
         }
       }
     }
-  } else {  // EPI_LMHEAD: softmax statistics of this wave's 128 columns per row
+  } else {  // EPI_LMHEAD / EPI_LMSAMPLE: softmax statistics of this wave's 128 columns per row
     f32x4* o = (f32x4*)out;
     const int nparts = nblocks * WGN;
     const int part = nblock * WGN + wn;
@@ -252,13 +251,21 @@ __global__ __launch_bounds__(WGN* WGM * 64) void gemm_bf16_tiled_kernel(
         w.w = __int_as_float(st.idx);
         o[(int64_t)m * nparts + part] = w;
       }
+      if constexpr (EPI == EPI_LMSAMPLE) {
+        RowPick pk = pick_empty();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pick_update_tile32(pk, acc[i][t], sc, n0 + 32 * i, hi, N, m, smp);
+        pk = pick_merge(pk, pick_shfl_xor(pk, 32));
+        if (hi == 0 && m < M) pick_store(smp, (int64_t)m * nparts + part, pk);
+      }
     }
   }
 }
 
 template <int WGN, int WGM, int WM>
 static hipError_t launch_tiled_shape(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale,
-                                     int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st) {
+                                     int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st,
+                                     const LmSample& smp) {
   constexpr int STAGE_KIB = 8 * WGN + 2 * WM * WGM;   // one k-step of the workgroup tile
   constexpr int NS = 4 * STAGE_KIB <= 144 ? 4 : 3;      // ring depth that fits the 160 KiB of LDS
   const int nblocks = (N / 16 + 8 * WGN - 1) / (8 * WGN);
@@ -269,20 +276,26 @@ static hipError_t launch_tiled_shape(const bf16_t* X, const bf16_t* Wp, void* ou
   const u32x4* W4 = (const u32x4*)Wp;
   if (epi == EPI_PARTIAL)
     hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WGN, WGM, WM, EPI_PARTIAL, NS>), grid, block, 0, st, X, W4,
-                       out, row_scale, M, N, Kd, kps, nblocks, plan.mblocks);
+                       out, row_scale, M, N, Kd, kps, nblocks, plan.mblocks, smp);
   else if (epi == EPI_SWIGLU)
     hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WGN, WGM, WM, EPI_SWIGLU, NS>), grid, block, 0, st, X, W4,
-                       out, row_scale, M, N, Kd, kps, nblocks, plan.mblocks);
-  else
+                       out, row_scale, M, N, Kd, kps, nblocks, plan.mblocks, smp);
+  else if (epi == EPI_LMHEAD)
     hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WGN, WGM, WM, EPI_LMHEAD, NS>), grid, block, 0, st, X, W4,
-                       out, row_scale, M, N, Kd, kps, nblocks, plan.mblocks);
+                       out, row_scale, M, N, Kd, kps, nblocks, plan.mblocks, smp);
+  else
+    hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WGN, WGM, WM, EPI_LMSAMPLE, NS>), grid, block, 0, st, X, W4,
+                       out, row_scale, M, N, Kd, kps, nblocks, plan.mblocks, smp);
   return hipGetLastError();
 }
 
 // plan.tiled selects the workgroup shape, see tiled_shape_rows().
 hipError_t launch_gemm_bf16_tiled(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale,
-                                  int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st) {
+                                  int M, int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st,
+                                  const LmSample& smp) {
   if (N % 16 != 0 || Kd % 32 != 0 || M < 1) return hipErrorInvalidValue;
+  if (epi < EPI_PARTIAL || epi > EPI_LMSAMPLE) return hipErrorInvalidValue;
+  if (epi == EPI_LMSAMPLE && smp.pick == nullptr) return hipErrorInvalidValue;
   if (plan.splits < 1 || (epi != EPI_PARTIAL && plan.splits != 1)) return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU && (N % 32 != 0)) return hipErrorInvalidValue;
   // every split must own at least one k-tile (the kernel's prologue assumes it)
@@ -290,10 +303,10 @@ hipError_t launch_gemm_bf16_tiled(const bf16_t* X, const bf16_t* Wp, void* out, 
   const int kps = (ktiles + plan.splits - 1) / plan.splits;
   if ((plan.splits - 1) * kps >= ktiles) return hipErrorInvalidValue;
   switch (plan.tiled) {
-    case 2: return launch_tiled_shape<2, 2, 2>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 3: return launch_tiled_shape<2, 2, 3>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 4: return launch_tiled_shape<2, 4, 2>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 6: return launch_tiled_shape<2, 4, 3>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+    case 2: return launch_tiled_shape<2, 2, 2>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 3: return launch_tiled_shape<2, 2, 3>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 4: return launch_tiled_shape<2, 4, 2>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 6: return launch_tiled_shape<2, 4, 3>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
   }
   return hipErrorInvalidValue;
 }

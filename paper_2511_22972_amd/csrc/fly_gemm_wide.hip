@@ -21,7 +21,6 @@
 // the weight ring in flight.
 #include "fly_common.h"
 
-typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 namespace {
 
@@ -70,7 +69,8 @@ __device__ __forceinline__ void wide_row_stat(RowStat& run, const f32x16& v, flo
 template <int MT, int EPI, int RING, int NWV, int CG>
 __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
     const bf16_t* __restrict__ X, const u32x4* __restrict__ Wp, void* __restrict__ out,
-    const float* __restrict__ row_scale, int M, int N, int Kd, int chunks_per_split, int nblocks) {
+    const float* __restrict__ row_scale, int M, int N, int Kd, int chunks_per_split, int nblocks,
+    LmSample smp) {
   constexpr int KC = WIDE_KC;
   constexpr int WGS = 2 * CG * NWV;  // 16-column strips per workgroup
   // Workgroups are dealt to the eight XCDs round-robin by linear id; consecutive
@@ -298,7 +298,7 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
         }
       }
     }
-  } else {  // EPI_LMHEAD: softmax statistics of this wave's 32 CG columns per row
+  } else {  // EPI_LMHEAD / EPI_LMSAMPLE: softmax statistics of this wave's 32 CG columns per row
     f32x4* o = (f32x4*)out;
     const int nparts = nblocks * NWV;
     const int part = nblock * NWV + wave;
@@ -318,13 +318,21 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
         w.w = __int_as_float(st.idx);
         o[(int64_t)m * nparts + part] = w;
       }
+      if constexpr (EPI == EPI_LMSAMPLE) {
+        RowPick pk = pick_empty();
+#pragma unroll
+        for (int cg = 0; cg < CG; ++cg) pick_update_tile32(pk, acc[cg][t], sc, n0 + 32 * cg, hi, N, m, smp);
+        pk = pick_merge(pk, pick_shfl_xor(pk, 32));
+        if (hi == 0 && m < M) pick_store(smp, (int64_t)m * nparts + part, pk);
+      }
     }
   }
 }
 
 template <int MT, int RING, int NWV, int CG>
 static hipError_t launch_wide_mt(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale, int M,
-                                 int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st) {
+                                 int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st,
+                                 const LmSample& smp) {
   constexpr int WGS = 2 * CG * NWV;
   const int nblocks = (N / 16 + WGS - 1) / WGS;
   const int nchunks = (Kd / 32 + WIDE_KC - 1) / WIDE_KC;
@@ -333,34 +341,39 @@ static hipError_t launch_wide_mt(const bf16_t* X, const bf16_t* Wp, void* out, c
   const u32x4* W4 = (const u32x4*)Wp;
   if (epi == EPI_PARTIAL)
     hipLaunchKernelGGL((gemm_bf16_wide_kernel<MT, EPI_PARTIAL, RING, NWV, CG>), grid, block, 0, st, X, W4, out,
-                       row_scale, M, N, Kd, cps, nblocks);
+                       row_scale, M, N, Kd, cps, nblocks, smp);
   else if (epi == EPI_SWIGLU)
     hipLaunchKernelGGL((gemm_bf16_wide_kernel<MT, EPI_SWIGLU, RING, NWV, CG>), grid, block, 0, st, X, W4, out,
-                       row_scale, M, N, Kd, cps, nblocks);
-  else
+                       row_scale, M, N, Kd, cps, nblocks, smp);
+  else if (epi == EPI_LMHEAD)
     hipLaunchKernelGGL((gemm_bf16_wide_kernel<MT, EPI_LMHEAD, RING, NWV, CG>), grid, block, 0, st, X, W4, out,
-                       row_scale, M, N, Kd, cps, nblocks);
+                       row_scale, M, N, Kd, cps, nblocks, smp);
+  else
+    hipLaunchKernelGGL((gemm_bf16_wide_kernel<MT, EPI_LMSAMPLE, RING, NWV, CG>), grid, block, 0, st, X, W4, out,
+                       row_scale, M, N, Kd, cps, nblocks, smp);
   return hipGetLastError();
 }
 
 // plan.wide = number of 32-row tiles (3, 4, 5, 6 or 8).
 hipError_t launch_gemm_bf16_wide(const bf16_t* X, const bf16_t* Wp, void* out, const float* row_scale, int M,
-                                 int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st) {
+                                 int N, int Kd, const GemmPlan& plan, int epi, hipStream_t st,
+                                 const LmSample& smp) {
   // Host-side shape checks: whole 16-column tiles and 32-row k-tiles, all rows
   // inside the one row block, every split owning at least one chunk.
   if (N % 16 != 0 || Kd % 32 != 0 || M < 1 || M > plan.wide * 32) return hipErrorInvalidValue;
-  if (epi != EPI_PARTIAL && epi != EPI_SWIGLU && epi != EPI_LMHEAD) return hipErrorInvalidValue;
+  if (epi < EPI_PARTIAL || epi > EPI_LMSAMPLE) return hipErrorInvalidValue;
+  if (epi == EPI_LMSAMPLE && smp.pick == nullptr) return hipErrorInvalidValue;
   if (plan.splits < 1 || (epi != EPI_PARTIAL && plan.splits != 1)) return hipErrorInvalidValue;
   if (epi == EPI_SWIGLU && N % 32 != 0) return hipErrorInvalidValue;
   const int nchunks = (Kd / 32 + WIDE_KC - 1) / WIDE_KC;
   const int cps = (nchunks + plan.splits - 1) / plan.splits;
   if ((plan.splits - 1) * cps >= nchunks) return hipErrorInvalidValue;
   switch (plan.wide) {
-    case 3: return launch_wide_mt<3, 7, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 4: return launch_wide_mt<4, 7, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 5: return launch_wide_mt<5, 5, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 6: return launch_wide_mt<6, 5, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
-    case 8: return launch_wide_mt<8, 4, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st);
+    case 3: return launch_wide_mt<3, 7, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 4: return launch_wide_mt<4, 7, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 5: return launch_wide_mt<5, 5, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 6: return launch_wide_mt<6, 5, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 8: return launch_wide_mt<8, 4, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
   }
   return hipErrorInvalidValue;
 }

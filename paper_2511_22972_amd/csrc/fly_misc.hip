@@ -245,20 +245,35 @@ hipError_t launch_qkv_epilogue(const float* partial, int splits, const float* ro
 // LM-head combine: merge the per-wave statistics of one row over all column
 // groups, then lse = m + ln s, H = ln s - t/s, h = H / ln V (Eq. 5),
 // p_top1 = 1/s (the argmax logit is m), argmax = lowest maximal index (Eq. 1).
+// With pick != NULL also the drawn token: the column of the largest
+// Gumbel-perturbed logit over all parts (lowest column on ties).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void lmhead_combine_kernel(const f32x4* __restrict__ partial,
                                                              int nparts, int V,
                                                              int32_t* __restrict__ argmax,
                                                              float* __restrict__ p_top1,
                                                              float* __restrict__ h_norm,
-                                                             float* __restrict__ lse) {
+                                                             float* __restrict__ lse,
+                                                             const float* __restrict__ pick,
+                                                             int32_t* __restrict__ sampled) {
   __shared__ RowStat wst[4];
+  __shared__ RowPick wpk[4];
   const int m = blockIdx.x;
   RowStat st = stat_empty();
+  RowPick pk = pick_empty();
   for (int p = threadIdx.x; p < nparts; p += 256) {
     f32x4 w = partial[(int64_t)m * nparts + p];
     RowStat o{w.x, w.y, w.z, __float_as_int(w.w)};
     st = stat_merge(st, o);
+    if (pick != nullptr) {
+      const float* pp = pick + 2 * ((int64_t)m * nparts + p);
+      pk = pick_merge(pk, RowPick{pp[0], __float_as_int(pp[1])});
+    }
+  }
+  if (pick != nullptr) {  // uniform over the workgroup
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) pk = pick_merge(pk, pick_shfl_xor(pk, off));
+    if ((threadIdx.x & 63) == 0) wpk[threadIdx.x >> 6] = pk;
   }
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) st = stat_merge(st, stat_shfl_xor(st, off));
@@ -272,13 +287,20 @@ __global__ __launch_bounds__(256) void lmhead_combine_kernel(const f32x4* __rest
     p_top1[m] = 1.0f / r.s;
     h_norm[m] = H / logf((float)V);
     if (lse != nullptr) lse[m] = r.m + ln_s;
+    if (pick != nullptr) {
+      RowPick q = pick_merge(pick_merge(wpk[0], wpk[1]), pick_merge(wpk[2], wpk[3]));
+      // a row whose logits are all -inf has no perturbed maximum: fall back to the argmax
+      sampled[m] = q.idx != 0x7fffffff ? q.idx : r.idx;
+    }
   }
 }
 
 hipError_t launch_lmhead_combine(const float* partial, int nparts, int M, int V, int32_t* argmax,
-                                 float* p_top1, float* h_norm, float* lse, hipStream_t st) {
+                                 float* p_top1, float* h_norm, float* lse, hipStream_t st,
+                                 const float* pick, int32_t* sampled) {
+  if ((pick == nullptr) != (sampled == nullptr)) return hipErrorInvalidValue;
   hipLaunchKernelGGL(lmhead_combine_kernel, dim3(M), dim3(256), 0, st, (const f32x4*)partial, nparts,
-                     V, argmax, p_top1, h_norm, lse);
+                     V, argmax, p_top1, h_norm, lse, pick, sampled);
   return hipGetLastError();
 }
 

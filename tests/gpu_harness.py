@@ -51,6 +51,23 @@ class GpuWorkload:
         return res
 
 
+def verify_sampled(wl: GpuWorkload, tokens: np.ndarray, row_scale: Optional[torch.Tensor], seed: int,
+                   offset: int, theta=None, W=None) -> Dict[str, np.ndarray]:
+    """fly_verify_block_sampled on a loaded workload."""
+    fb, cfg = wl.fb, wl.cfg
+    tok = torch.as_tensor(np.ascontiguousarray(tokens), dtype=torch.int32).cuda()
+    rs = None if row_scale is None else row_scale.to("cuda", torch.float32).contiguous()
+    out = fb.VerifyOutputs(cfg.batch, cfg.K, cfg.d)
+    sampled = torch.zeros(cfg.batch, cfg.K + 1, dtype=torch.int32, device="cuda")
+    fb.fly_verify_block_sampled(wl.model, wl.kv, tok, rs, cfg.theta if theta is None else theta,
+                                cfg.window if W is None else W, seed, offset, sampled, out, wl.ws)
+    torch.cuda.synchronize()
+    res = {k: getattr(out, k).cpu().numpy() for k in
+           ("accept_len", "next_token", "kv_len_out", "n_loose", "argmax", "h_norm", "p_top1", "lse")}
+    res["sampled"] = sampled.cpu().numpy()
+    return res
+
+
 def ambiguous_rows(oracle_out: Dict[str, np.ndarray], theta: float, tol: float = 1e-3) -> np.ndarray:
     """[B, K+1] mask of positions whose integer outcome may legitimately differ:
     top-2 logit margin or entropy-minus-threshold below `tol`."""
