@@ -411,13 +411,25 @@ def main():
                                      lm_out.p_top1.view(-1), lm_out.h_norm.view(-1), None, lm_ws)
 
     lm_ms = time_region(lmhead, max(args.steps, 20), 4)
+    # the same with a token drawn per row (temperature > 0), fused into the same epilogue
+    lm_sampled = torch.zeros(cfg.M, dtype=torch.int32, device="cuda")
+    draw = [0]
+
+    def lmhead_sampled():
+        draw[0] += 1
+        fb.fly_lmhead_entropy_sample(hidden, model.w_lm, row_scale, cfg.vocab, cfg.seed, draw[0], lm_sampled,
+                                     lm_out.argmax.view(-1), lm_out.p_top1.view(-1), lm_out.h_norm.view(-1),
+                                     None, lm_ws)
+
+    lms_ms = time_region(lmhead_sampled, max(args.steps, 20), 4)
     lm_bytes = cfg.d * cfg.vocab * es + cfg.M * cfg.d * es
     lm_flops = 2.0 * cfg.M * cfg.d * cfg.vocab
     mfma_peak = MFMA_PEAK_TFLOPS if cfg.dtype == "bf16" else F32_PEAK_TFLOPS
     lm_head = {"avg_launch_us": lm_ms * 1e3, "flops_per_launch": lm_flops, "bytes_per_launch": lm_bytes,
                "achieved_TFLOPs": lm_flops / (lm_ms * 1e-3) / 1e12, "achieved_GBps": lm_bytes / (lm_ms * 1e-3) / 1e9,
                "frac_of_mfma_peak": lm_flops / (lm_ms * 1e-3) / 1e12 / mfma_peak,
-               "frac_of_hbm_peak": lm_bytes / (lm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+               "frac_of_hbm_peak": lm_bytes / (lm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+               "with_drawn_token_us": lms_ms * 1e3}
     # Up to 256 rows every GEMM is bound by streaming its weights (the weight-
     # streaming kernels; 256 flop per weight byte is still below the ridge) and the
     # dominant kernel is gate/up.  Beyond that the GEMMs are dense contractions
