@@ -100,6 +100,35 @@ def test_lmhead_argument_checks(fb):
     assert f(p, p, None, 0, 8192, 128256, 1, p, p, p, None, p, need, None) == -2
 
 
+def test_sampled_entry_points_argument_checks(fb):
+    """The entry points with a drawn token share the checks of the plain ones and need `sampled`."""
+    p = C.c_void_p(4096)
+    f = fb.lib.fly_lmhead_entropy_sample
+    out = C.c_size_t(0)
+    assert fb.lib.fly_lmhead_workspace_bytes(36, 8192, 128256, fb.FLY_BF16, C.byref(out)) == 0
+    need = out.value
+    assert need >= 36 * (128256 // 64) * 24      # statistics and the pick per row and 64 columns
+    assert f(p, p, None, 36, 8192, 128256, 1, 7, 0, None, p, p, p, None, p, need, None) == -1
+    assert f(None, p, None, 36, 8192, 128256, 1, 7, 0, p, p, p, p, None, p, need, None) == -1
+    assert f(p, p, None, 36, 8192, 128256, 1, 7, 0, p, p, p, p, None, p, need - 1, None) == -9
+    assert f(p, p, None, 36, 8192, 128250, 1, 7, 0, p, p, p, p, None, p, need, None) == -2
+    q = 4096
+    d = _desc(fb)
+    lw = (fb.fly_layer_weights * 2)(*[fb.fly_layer_weights(q, q, q, q, q, q)] * 2)
+    w = fb.fly_weights(q, lw, q, q)
+    karr = (C.c_void_p * 2)(q, q)
+    kv = fb.fly_kv_cache(karr, karr, q, 192, 128)
+    vout = fb.fly_verify_out(q, q, q, q, q, q, None, None, None)
+    ws = C.c_size_t(0)
+    fb.lib.fly_workspace_bytes(C.byref(d), 1, 4, 128, C.byref(ws))
+    g = fb.lib.fly_verify_block_sampled
+    base = [C.byref(d), C.byref(w), C.byref(kv), q, None, 1, 4, 0.3, 6, 1, 2]
+    assert g(*base, None, C.byref(vout), q, ws.value, None) == -1
+    assert g(*base, q, C.byref(vout), q, ws.value - 1, None) == -9
+    base[6] = 70
+    assert g(*base, q, C.byref(vout), q, ws.value, None) == -3
+
+
 def test_verify_block_argument_checks(fb):
     p = 4096
     d = _desc(fb)
