@@ -267,14 +267,17 @@ def philox4x32_10(counter: np.ndarray, key: Tuple[int, int]) -> np.ndarray:
     return np.stack([c0, c1, c2, c3], axis=-1).astype(np.uint32)
 
 
-def sample_bits(M: int, V: int, seed: int, offset: int) -> np.ndarray:
+def sample_bits(M: int, V: int, seed: int, offset: int, rows=None) -> np.ndarray:
     """The 32 random bits of every (row m, column v) of one call: word v % 4 of the
     Philox block with counter (v // 4, m, offset low, offset high) and key
-    (seed low, seed high).  `offset` tells calls with the same seed apart."""
+    (seed low, seed high).  `offset` tells calls with the same seed apart.
+    `rows` (default 0..M-1) names the rows m of the call that the M output rows stand for."""
     nblk = (V + 3) // 4
+    row_ids = np.arange(M, dtype=np.uint64) if rows is None else np.asarray(rows, dtype=np.uint64)
+    assert row_ids.shape == (M,)
     ctr = np.zeros((M, nblk, 4), dtype=np.uint64)
     ctr[..., 0] = np.arange(nblk, dtype=np.uint64)[None, :]
-    ctr[..., 1] = np.arange(M, dtype=np.uint64)[:, None]
+    ctr[..., 1] = row_ids[:, None]
     ctr[..., 2] = offset & 0xFFFFFFFF
     ctr[..., 3] = (offset >> 32) & 0xFFFFFFFF
     bits = philox4x32_10(ctr, (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF))
@@ -291,7 +294,7 @@ def gumbel_noise(bits: np.ndarray) -> np.ndarray:
     return -np.log(-np.log(uniform_open01(bits)))
 
 
-def sample_rows(logits: np.ndarray, seed: int, offset: int) -> Dict[str, np.ndarray]:
+def sample_rows(logits: np.ndarray, seed: int, offset: int, rows=None) -> Dict[str, np.ndarray]:
     """One draw per row from softmax(logits[m]) by the Gumbel-max construction:
     argmax_v (l_v + G_v) with independent standard Gumbel G_v is distributed as
     softmax(l).  The decision is taken in float32 (float32 logits plus float32
@@ -299,10 +302,11 @@ def sample_rows(logits: np.ndarray, seed: int, offset: int) -> Dict[str, np.ndar
 
     token   -- the drawn column per row
     margin  -- largest minus second-largest perturbed logit (near-tie diagnostic)
+    `rows`: the row numbers within the call, when `logits` holds only some of its rows.
     """
     l = np.asarray(logits, dtype=np.float64)
     M, V = l.shape
-    g = gumbel_noise(sample_bits(M, V, seed, offset))
+    g = gumbel_noise(sample_bits(M, V, seed, offset, rows))
     z = l.astype(np.float32) + g.astype(np.float32)
     token = np.argmax(z, axis=1).astype(np.int64)
     if V > 1:

@@ -117,6 +117,16 @@ def lmhead_full(cfg, M, sample_rows=None):
     near_tie = ref["margin"] < 1e-3
     assert np.all((got["argmax"] == ref["argmax"]) | near_tie)
     assert ref["h"].min() < 0.3 < ref["h"].max()
+    # the same launch shape with a token drawn per row (temperature > 0)
+    sampled = torch.zeros(M, dtype=torch.int32, device="cuda")
+    argmax2 = torch.zeros(M, dtype=torch.int32, device="cuda")
+    fb.fly_lmhead_entropy_sample(hidden, wp, rs, V, cfg.seed, 5, sampled, argmax2, p1, hn, lse, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(argmax2, argmax)
+    drawn = O.sample_rows(logits.numpy(), cfg.seed, 5, rows=rows)
+    ok = (sampled.cpu().numpy()[rows] == drawn["token"]) | (drawn["margin"] < 1e-3)
+    assert np.all(ok), np.argwhere(~ok)
+    assert (drawn["token"] != ref["argmax"]).any()
     return got, ref, rs
 
 

@@ -49,6 +49,16 @@ def test_sample_bits_layout():
             assert int(bits[m, v]) == int(blk[0, v % 4])
 
 
+def test_a_subset_of_rows_draws_what_the_whole_call_draws():
+    rng = np.random.default_rng(5)
+    logits = rng.normal(size=(40, 64))
+    whole = O.sample_rows(logits, 21, 8)
+    rows = [3, 17, 39]
+    part = O.sample_rows(logits[rows], 21, 8, rows=rows)
+    assert np.array_equal(part["token"], whole["token"][rows])
+    assert np.allclose(part["margin"], whole["margin"][rows])
+
+
 def test_uniform_is_strictly_inside_the_unit_interval_and_exact_in_float32():
     edge = np.array([0, 1, 511, 512, 2**32 - 1, 2**31], dtype=np.uint32)
     u = O.uniform_open01(edge)
