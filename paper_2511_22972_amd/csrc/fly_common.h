@@ -84,6 +84,37 @@ __device__ __forceinline__ RowStat stat_shfl_xor(const RowStat& a, int o) {
   return r;
 }
 
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+// Softmax statistics of the sixteen logits a lane holds of one 32 x 32 tile (columns
+// n0 + 8 (r/4) + 4 hi + r%4 of one row), folded into the row's running statistics.
+__device__ __forceinline__ void stat_update_tile32(RowStat& run, const f32x16& v, float sc, int n0, int hi,
+                                                   int N) {
+  float mx = -INFINITY;
+  int idx = 0x7fffffff;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int n = n0 + 8 * (r >> 2) + 4 * hi + (r & 3);
+    const float x = v[r] * sc;
+    if (n < N && x > mx) {
+      mx = x;
+      idx = n;
+    }
+  }
+  if (idx == 0x7fffffff) return;  // tile entirely past the last column
+  RowStat st{mx, 0.f, 0.f, idx};
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    const int n = n0 + 8 * (r >> 2) + 4 * hi + (r & 3);
+    if (n < N) {
+      const float dlt = v[r] * sc - mx;
+      const float e = __expf(dlt);
+      st.s += e;
+      st.t += dlt * e;
+    }
+  }
+  run = stat_merge(run, st);
+}
+
 // ---- drawing a token from the softmax of the scaled logits -----------------
 // The paper reports temperature-1 results (Tables 1-2) and states its rule with
 // the argmax only (Eqs. 1-2); here the drawn token takes the argmax's place.
@@ -151,9 +182,8 @@ __device__ __forceinline__ void pick_update4(RowPick& p, float v0, float v1, flo
     }
   }
 }
-// The sixteen logits a lane holds of one 32 x 32 matrix-core tile: columns
-// n0 + 8 (r/4) + 4 hi + r%4 of one row, i.e. four aligned groups of four.
-typedef __attribute__((ext_vector_type(16))) float f32x16;
+// The sixteen logits a lane holds of one 32 x 32 matrix-core tile (see stat_update_tile32) are
+// four aligned groups of four columns.
 __device__ __forceinline__ void pick_update_tile32(RowPick& p, const f32x16& v, float sc, int n0, int hi,
                                                    int N, int row, const LmSample& smp) {
 #pragma unroll

@@ -13,7 +13,6 @@
 // barrier per k-step.
 #include "fly_common.h"
 
-
 namespace {
 
 __device__ __forceinline__ float silu_t(float x) { return x / (1.f + __expf(-x)); }
@@ -59,36 +58,6 @@ __device__ __forceinline__ void tiled_mma(const TiledFrags<WM>& f, f32x16 (&acc)
 #pragma unroll
     for (int t = 0; t < WM; ++t)
       acc[i][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.w[i], f.x[t], acc[i][t], 0, 0, 0);
-}
-
-// Softmax statistics of the 32 logits a lane holds of one 32 x 32 tile (columns
-// n0 + 8 (r/4) + 4 hi + r%4 of one row), folded into the row's running statistics.
-__device__ __forceinline__ void tile_row_stat(RowStat& run, const f32x16& v, float sc, int n0, int hi,
-                                              int N) {
-  float mx = -INFINITY;
-  int idx = 0x7fffffff;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int n = n0 + 8 * (r >> 2) + 4 * hi + (r & 3);
-    const float x = v[r] * sc;
-    if (n < N && x > mx) {
-      mx = x;
-      idx = n;
-    }
-  }
-  if (idx == 0x7fffffff) return;  // tile entirely past the last column
-  RowStat st{mx, 0.f, 0.f, idx};
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int n = n0 + 8 * (r >> 2) + 4 * hi + (r & 3);
-    if (n < N) {
-      const float dlt = v[r] * sc - mx;
-      const float e = __expf(dlt);
-      st.s += e;
-      st.t += dlt * e;
-    }
-  }
-  run = stat_merge(run, st);
 }
 
 }  // namespace
@@ -241,7 +210,7 @@ __global__ __launch_bounds__(WGN* WGM * 64) void gemm_bf16_tiled_kernel(
       const float sc = (row_scale != nullptr && m < M) ? row_scale[m] : 1.f;
       RowStat st = stat_empty();
 #pragma unroll
-      for (int i = 0; i < 4; ++i) tile_row_stat(st, acc[i][t], sc, n0 + 32 * i, hi, N);
+      for (int i = 0; i < 4; ++i) stat_update_tile32(st, acc[i][t], sc, n0 + 32 * i, hi, N);
       st = stat_merge(st, stat_shfl_xor(st, 32));
       if (hi == 0 && m < M) {
         f32x4 w;

@@ -15,12 +15,16 @@
 // v_mfma_f32_32x32x16_bf16 (MT = 3, 4, 5, 6 or 8 tiles of 32 rows; weights = A
 // operand, activations = B operand, out^T[n, m] = sum_k W[k, n] X[m, k]).  Two
 // waves share a SIMD, so one multiplies while the other waits for its weights.
-// Only the small activation block goes through LDS, copied there by LDS-direct
-// loads two chunks ahead, which keeps it out of the registers and, unlike a
-// register copy that must be waited for before it can be written to LDS, leaves
-// the weight ring in flight.
+// Only the small activation block goes through LDS: every wave fetches its
+// share of it into registers two chunks ahead and writes it to LDS one chunk
+// ahead.  All loads of the kernel are ordinary register loads, so the compiler
+// places every wait.  (An earlier form copied the activations with LDS-direct
+// loads and counted the waits by hand, assuming that a wave's LDS-direct loads
+// and its register loads complete in issue order relative to each other.  They do
+// not on this chip: with activations that miss the L2 -- the down projection at the
+// 405B width -- about one launch in twelve read an activation stage that had not
+// landed yet.)
 #include "fly_common.h"
-
 
 namespace {
 
@@ -30,36 +34,6 @@ constexpr int WIDE_CG = 1;   // 32-column groups per wave
 constexpr int WIDE_COLS = 32 * WIDE_CG * WIDE_NWV;
 
 __device__ __forceinline__ float silu_w(float x) { return x / (1.f + __expf(-x)); }
-
-// Softmax statistics of the 16 logits a lane holds of one 32 x 32 tile (columns
-// n0 + 8 (r/4) + 4 hi + r%4 of one row), folded into the row's running statistics.
-__device__ __forceinline__ void wide_row_stat(RowStat& run, const f32x16& v, float sc, int n0, int hi,
-                                              int N) {
-  float mx = -INFINITY;
-  int idx = 0x7fffffff;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int n = n0 + 8 * (r >> 2) + 4 * hi + (r & 3);
-    const float x = v[r] * sc;
-    if (n < N && x > mx) {
-      mx = x;
-      idx = n;
-    }
-  }
-  if (idx == 0x7fffffff) return;  // tile entirely past the last column
-  RowStat st{mx, 0.f, 0.f, idx};
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int n = n0 + 8 * (r >> 2) + 4 * hi + (r & 3);
-    if (n < N) {
-      const float dlt = v[r] * sc - mx;
-      const float e = __expf(dlt);
-      st.s += e;
-      st.t += dlt * e;
-    }
-  }
-  run = stat_merge(run, st);
-}
 
 }  // namespace
 
@@ -78,13 +52,12 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
   const int nblock = blockIdx.x;
   if (nblock >= nblocks) return;
 
-  // LDS: ring of NSTG activation blocks.  One k-tile (32 wide) of 16 rows is
-  // 1 KiB: a row is four 16-byte pieces, piece c of row r at position
-  // 4 r + (c ^ ((r >> 1) & 3)), so that the operand reads of eight consecutive
-  // rows fall into distinct banks.  Group 2 MT is a dummy target of surplus pieces.
-  constexpr int XD = 2;          // the activation block is requested XD chunks ahead
-  constexpr int NSTG = XD + 1;
-  __shared__ u32x4 xs[NSTG][KC][2 * MT + 1][64];
+  // LDS: two activation blocks (the one being multiplied, the one being written).
+  // One k-tile (32 wide) of 16 rows is 1 KiB: a row is four 16-byte pieces, piece c
+  // of row r at position 4 r + (c ^ ((r >> 1) & 3)), so that the operand reads of
+  // eight consecutive rows fall into distinct banks.
+  static_assert(RING % 2 == 0, "the register buffers of the activations alternate with the ring");
+  __shared__ u32x4 xs[2][KC][2 * MT][64];
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -124,37 +97,39 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
     }
   };
 
-  // Activation pieces this wave copies per chunk, global memory straight into
-  // LDS: piece f = wave + NWV i is k-tile f / (2 MT), row group f % (2 MT); lane
-  // 4 r + c' fetches row r of the group, 16-byte piece c' ^ ((r >> 1) & 3), and
-  // the wave's 1 KiB lands in lane order.  Every wave issues NXL loads (the
-  // hand-counted waits below rely on it): surplus ones re-load the last piece
-  // into the dummy group.  Rows past M are clamped to row M-1 (they feed output
-  // rows that are never stored), k-tiles past the end to the last valid one
-  // (they meet zeroed weight fragments).
+  // Activation pieces this wave copies per chunk: piece f = wave + NWV i is k-tile
+  // f / (2 MT), row group f % (2 MT); lane 4 r + c' fetches row r of the group,
+  // 16-byte piece c' ^ ((r >> 1) & 3), and the wave's 1 KiB is stored in lane
+  // order.  Rows past M are clamped to row M-1 (they feed output rows that are
+  // never stored), k-tiles past the end to the last valid one (they meet zeroed
+  // weight fragments).  A wave whose last piece index falls past the block loads
+  // the last piece again and does not store it (the loads stay unconditional so that
+  // the compiler can count exactly how many were issued after the one it waits for).
   constexpr int NPIECE = KC * 2 * MT;
   constexpr int NXL = (NPIECE + NWV - 1) / NWV;
-  constexpr int NWL = CG * KC * 2;  // weight loads per wave and chunk
-  const bf16_t* xrow[NXL];
+  const u32x4* xrow[NXL];
   int xkt[NXL], xgrp[NXL];
 #pragma unroll
   for (int i = 0; i < NXL; ++i) {
-    const int f = wave + NWV * i;
-    const int fc = min(f, NPIECE - 1);
+    const int fc = min(wave + NWV * i, NPIECE - 1);
     xkt[i] = fc / (2 * MT);
-    xgrp[i] = f < NPIECE ? fc % (2 * MT) : 2 * MT;
+    xgrp[i] = fc % (2 * MT);
     const int r = lane >> 2;
     const int piece = (lane & 3) ^ ((r >> 1) & 3);
-    const int row = min((fc % (2 * MT)) * 16 + r, M - 1);
-    xrow[i] = X + (int64_t)row * Kd + piece * 8;
+    const int row = min(xgrp[i] * 16 + r, M - 1);
+    xrow[i] = (const u32x4*)(X + (int64_t)row * Kd + piece * 8);
   }
-  auto issue_x = [&](int chunk, int stage) {
-    asm volatile("" : "+s"(stage));  // keep the LDS address a register value (a folded constant is no valid asm operand)
+  auto load_x = [&](u32x4 (&xb)[NXL], int chunk) {
 #pragma unroll
     for (int i = 0; i < NXL; ++i) {
       const int k = min(chunk * KC + xkt[i], kt_last);
-      FLY_GLOBAL_TO_LDS16(xrow[i] + (int64_t)k * 32, &xs[stage][xkt[i]][xgrp[i]][0]);
+      xb[i] = xrow[i][(int64_t)k * 4];  // 32 bf16 per k-tile = four pieces
     }
+  };
+  auto store_x = [&](const u32x4 (&xb)[NXL], int stage) {
+#pragma unroll
+    for (int i = 0; i < NXL; ++i)
+      if (wave + NWV * i < NPIECE) xs[stage][xkt[i]][xgrp[i]][lane] = xb[i];
   };
 
   f32x16 acc[CG][MT];
@@ -210,46 +185,46 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
 
   // Software pipeline over k-chunks.  Weights: a ring of RING register buffers;
   // while chunk c is multiplied, chunks c+1 .. c+RING-1 are in flight.
-  // Activations: chunk c+XD is requested in step c and must have landed, for
-  // every wave, when step c+1 begins; the loads of a wave complete in order,
-  // so waiting until at most NWL + (XD-1)(NXL+NWL) loads are outstanding (those
-  // issued after the activation loads of chunk c+1) is enough, and the weight
-  // ring stays in flight (activations fetched through registers would have to be
-  // waited for before they can be written to LDS, which drains the ring down to
-  // its youngest chunk at every step).  The compiler does not know of the
-  // LDS-direct loads; its own waits for the weight registers therefore count
-  // too few loads behind them and wait a little longer than needed, never
-  // shorter.  The barrier at the end of a step also says that every wave is
-  // done reading stage c % NSTG, which step c+1 refills.
+  // Activations: step c requests chunk c+2 into one of two register buffers,
+  // multiplies chunk c out of LDS stage c % 2 and then writes chunk c+1 (requested in
+  // step c-1) from the other register buffer into stage (c+1) % 2, which every wave
+  // finished reading before the barrier that ended step c-1.  The wait for those
+  // registers leaves everything issued after them in flight: the weights requested in
+  // steps c-1 and c and the activations of chunk c+2.  The workgroup barrier is the bare
+  // instruction (a __syncthreads would also wait for every outstanding load); the
+  // explicit wait before it completes this wave's LDS writes and reads.
   u32x4 ring[RING][CG][KC][2];
-  auto step = [&](const u32x4 (&cur)[CG][KC][2], u32x4 (&refill)[CG][KC][2], int chunk) {
-    issue_x(chunk + XD, (chunk - chunk_begin + XD) % NSTG);
+  u32x4 xb[2][NXL];
+  auto step = [&](const u32x4 (&cur)[CG][KC][2], u32x4 (&refill)[CG][KC][2], u32x4 (&xnew)[NXL],
+                  const u32x4 (&xnext)[NXL], int chunk) {
+    load_x(xnew, chunk + 2);
     __builtin_amdgcn_sched_barrier(0);
     load_w(refill, chunk + RING - 1);
     __builtin_amdgcn_sched_barrier(0);
-    compute(cur, chunk, (chunk - chunk_begin) % NSTG);
-    FLY_WAIT_VMCNT(NWL + (XD - 1) * (NXL + NWL));
+    compute(cur, chunk, (chunk - chunk_begin) & 1);
+    store_x(xnext, (chunk - chunk_begin + 1) & 1);
     FLY_WAIT_LGKMCNT0();
     FLY_BARE_BARRIER();
   };
   if (chunk_begin < chunk_end) {
-#pragma unroll
-    for (int j = 0; j < XD; ++j) issue_x(chunk_begin + j, j);
+    load_x(xb[0], chunk_begin);
+    load_x(xb[1], chunk_begin + 1);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int r = 0; r < RING - 1; ++r) load_w(ring[r], chunk_begin + r);
-    FLY_WAIT_VMCNT((RING - 1) * NWL + (XD - 1) * NXL);  // the activations of the first chunk
+    store_x(xb[0], 0);
+    FLY_WAIT_LGKMCNT0();
     FLY_BARE_BARRIER();
+    // step r of a round of RING steps (RING even) refills register buffer r % 2
     int c = chunk_begin;
     while (c + RING <= chunk_end) {
 #pragma unroll
-      for (int r = 0; r < RING; ++r) step(ring[r], ring[(r + RING - 1) % RING], c + r);
+      for (int r = 0; r < RING; ++r) step(ring[r], ring[(r + RING - 1) % RING], xb[r & 1], xb[(r + 1) & 1], c + r);
       c += RING;
     }
 #pragma unroll
     for (int r = 0; r < RING - 1; ++r)
-      if (c + r < chunk_end) step(ring[r], ring[(r + RING - 1) % RING], c + r);
-    FLY_WAIT_VMCNT(0);  // surplus (clamped) loads must have landed before the wave may end
+      if (c + r < chunk_end) step(ring[r], ring[(r + RING - 1) % RING], xb[r & 1], xb[(r + 1) & 1], c + r);
   }
 
   // ---- epilogues.  Accumulator register r of tile (cg, t) in lane l is
@@ -308,7 +283,7 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
       const float sc = (row_scale != nullptr && m < M) ? row_scale[m] : 1.f;
       RowStat st = stat_empty();
 #pragma unroll
-      for (int cg = 0; cg < CG; ++cg) wide_row_stat(st, acc[cg][t], sc, n0 + 32 * cg, hi, N);
+      for (int cg = 0; cg < CG; ++cg) stat_update_tile32(st, acc[cg][t], sc, n0 + 32 * cg, hi, N);
       st = stat_merge(st, stat_shfl_xor(st, 32));
       if (hi == 0 && m < M) {
         f32x4 w;
@@ -369,11 +344,11 @@ hipError_t launch_gemm_bf16_wide(const bf16_t* X, const bf16_t* Wp, void* out, c
   const int cps = (nchunks + plan.splits - 1) / plan.splits;
   if ((plan.splits - 1) * cps >= nchunks) return hipErrorInvalidValue;
   switch (plan.wide) {
-    case 3: return launch_wide_mt<3, 7, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
-    case 4: return launch_wide_mt<4, 7, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
-    case 5: return launch_wide_mt<5, 5, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
-    case 6: return launch_wide_mt<6, 5, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
-    case 8: return launch_wide_mt<8, 4, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 3: return launch_wide_mt<3, 6, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 4: return launch_wide_mt<4, 6, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 5: return launch_wide_mt<5, 4, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 6: return launch_wide_mt<6, 4, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
+    case 8: return launch_wide_mt<8, 2, WIDE_NWV, WIDE_CG>(X, Wp, out, row_scale, M, N, Kd, plan, epi, st, smp);
   }
   return hipErrorInvalidValue;
 }

@@ -92,6 +92,32 @@ def test_paper_sized_blocks_one_layer_full_width(name):
     one_layer_case(synth.CONFIGS[name])
 
 
+@pytest.mark.parametrize("M", [136, 256])
+def test_down_projection_405b_width_is_reproducible(M):
+    """The down projection at the 405B width (53248 -> 16384): its activation block does not fit
+    the L2, so the loads of one wave return in every order the memory system allows.  Forty
+    launches must give the same bits, and the sum of the split-K partials the product.  (A form of
+    the 81..256-row kernel that counted the waits for its activation copies by hand failed this in
+    about one launch out of twelve.)"""
+    from paper_2511_22972_amd import binding as fb
+    cfg = synth.CONFIGS["c4_405b_slice"]
+    Kd, N = cfg.ffn, cfg.d
+    w = synth.hash_normal(cfg.seed, 400, (Kd, N), 0.02, torch.bfloat16, "cuda")
+    wp = torch.empty(Kd * N, dtype=torch.bfloat16, device="cuda")
+    fb.fly_pack_weight(w, wp, N)
+    xa = synth.hash_normal(cfg.seed, 313, (M, Kd), 1.0, torch.bfloat16, "cuda")
+    part = torch.empty(16 * M * N, dtype=torch.float32, device="cuda")
+    splits = fb.fly_proj_partial(xa, wp, part, N)
+    torch.cuda.synchronize()
+    first = part[: splits * M * N].clone()
+    ref = xa.float() @ w.float()
+    assert float((first.view(splits, M, N).sum(0) - ref).abs().max()) < 2e-3
+    for i in range(40):
+        assert fb.fly_proj_partial(xa, wp, part, N) == splits
+        torch.cuda.synchronize()
+        assert torch.equal(part[: splits * M * N], first), i
+
+
 def lmhead_full(cfg, M, sample_rows=None):
     from paper_2511_22972_amd import binding as fb
     d, V = cfg.d, cfg.vocab
