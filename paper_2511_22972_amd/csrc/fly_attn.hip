@@ -49,7 +49,9 @@
 // which cannot tell the ring slots apart, does not wait for ALL outstanding
 // loads before every LDS read; the waits for these loads are placed by hand.
 // Unknown to the compiler's counters, they can only make its own vmcnt waits
-// longer than needed, never shorter (loads complete in order).  M0 is reserved
+// longer than needed, never shorter.  The hand-counted waits rely on LDS-direct
+// loads completing in issue order among themselves; no register load is in
+// flight while they count (the query loads are waited for first).  M0 is reserved
 // by the compiler, which warns about the clobber; nothing else here uses M0.
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"

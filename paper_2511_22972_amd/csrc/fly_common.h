@@ -211,7 +211,11 @@ __device__ __forceinline__ void pick_store(const LmSample& smp, int64_t slot, co
 // insertion cannot tell the ring slots apart and would wait for ALL outstanding
 // loads before every LDS read; the waits for these loads are placed by hand
 // (FLY_WAIT_VMCNT).  Unknown to the compiler's counters, they can only make its
-// own vmcnt waits longer than needed, never shorter (loads complete in order).
+// own vmcnt waits longer than needed, never shorter (register loads complete in
+// order among themselves, and so do LDS-direct loads).  Between the two kinds
+// there is NO order on this chip: a hand-counted wait is valid only while no
+// register load of the wave is in flight (measured: a kernel that mixed them
+// read LDS stages that had not landed).
 // (M0 is reserved by the compiler, which warns about the clobber; nothing else
 // in this file uses M0, and the clobber makes the compiler reload it if it did.)
 #pragma clang diagnostic push

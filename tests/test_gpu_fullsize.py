@@ -118,6 +118,46 @@ def test_down_projection_405b_width_is_reproducible(M):
         assert torch.equal(part[: splits * M * N], first), i
 
 
+def test_kernels_with_hand_counted_waits_are_reproducible():
+    """The LDS-tiled GEMM and the attention kernel count the waits for their LDS-direct loads by hand.
+    At sizes that miss every cache (1088 x 28672 activations, a 32768-key cache) twenty launches must
+    give the same bits, and the GEMM the product."""
+    from paper_2511_22972_amd import binding as fb
+    M, Kd, N = 1088, 28672, 8192
+    xa = synth.hash_normal(1, 5, (M, Kd), 1.0, torch.bfloat16, "cuda")
+    w = synth.hash_normal(1, 6, (Kd, N), 0.02, torch.bfloat16, "cuda")
+    wp = torch.empty(Kd * N, dtype=torch.bfloat16, device="cuda")
+    fb.fly_pack_weight(w, wp, N)
+    part = torch.empty(16 * M * N, dtype=torch.float32, device="cuda")
+    splits = fb.fly_proj_partial(xa, wp, part, N)
+    torch.cuda.synchronize()
+    first = part[: splits * M * N].clone()
+    assert float((first.view(splits, M, N).sum(0) - xa.float() @ w.float()).abs().max()) < 2e-3
+    for i in range(20):
+        fb.fly_proj_partial(xa, wp, part, N)
+        torch.cuda.synchronize()
+        assert torch.equal(part[: splits * M * N], first), i
+    del xa, w, wp, part, first
+    cfg = C5.replace(n_layers=1, batch=16)
+    desc = fb.make_desc(cfg)
+    cap = (cfg.kv_len + cfg.K + 1 + 63) // 64 * 64
+    kv = fb.KVCache(desc, cfg.batch, cap)
+    kv.k[0].normal_()
+    kv.v[0].normal_()
+    kv.set_lengths([cfg.kv_len] * cfg.batch)
+    q = synth.hash_normal(2, 7, (cfg.M, cfg.q_dim), 1.0, torch.bfloat16, "cuda")
+    o = torch.empty_like(q)
+    ws = fb.alloc_workspace(fb.fly_workspace_bytes(desc, cfg.batch, cfg.K, cfg.kv_len))
+    fb.fly_attention(desc, kv, 0, q, o, cfg.batch, cfg.K, ws)
+    torch.cuda.synchronize()
+    first = o.clone()
+    assert torch.isfinite(first.float()).all()
+    for i in range(20):
+        fb.fly_attention(desc, kv, 0, q, o, cfg.batch, cfg.K, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(o, first), i
+
+
 def lmhead_full(cfg, M, sample_rows=None):
     from paper_2511_22972_amd import binding as fb
     d, V = cfg.d, cfg.vocab
