@@ -31,12 +31,16 @@
 #define ATT_NWAVES 8
 #define ATT_NSTG 4                      // stages in the LDS ring (128 KiB); three are in flight
 // Rows are stored unpadded; the 16-byte pieces of a row are permuted so that
-// the operand-order loads of eight consecutive lanes spread over all banks.
-// Key rows XOR the piece index with the low four bits of the key, bit 2
-// flipped when bit 3 is set (a lane octet reads keys k..k+3 and k+8..k+11, see
-// ATT_KPERM); V^T rows XOR it with (row & 7).
+// the operand-order loads are free of bank conflicts.  A 128-bit LDS read serves
+// sixteen lanes per cycle (256 bytes, 64 banks): lanes 0-7 together with 24-31,
+// 8-15 with 16-23, and the same in the upper half-wave (measured).  Key rows
+// (256 bytes) XOR the piece index with the low four bits of the key, bit 2
+// flipped when bit 3 is set: the sixteen keys such a lane set reads (see
+// ATT_KPERM) then take sixteen distinct pieces.  V^T rows (128 bytes, so the row's
+// parity is the top bit of the phase) XOR it with (row & 7), bit 0 flipped for rows
+// 16-31 of a 32-row tile: rows 0-7 and 24-31, and 8-15 and 16-23, never meet.
 #define ATT_KSWZ(key, piece) (((piece) ^ (((key) & 15) ^ ((((key) >> 3) & 1) << 2))) * 16)
-#define ATT_VSWZ(row, piece) (((piece) ^ ((row) & 7)) * 16)
+#define ATT_VSWZ(row, piece) (((piece) ^ (((row) & 7) ^ (((row) >> 4) & 1))) * 16)
 // Row i of a 32-key score tile holds key ATT_KPERM(i) of the tile (bits 2 and 3
 // of i swapped).  With this order the sixteen scores a lane holds of one query
 // row are two runs of eight consecutive keys, i.e. exactly the operand order

@@ -21,8 +21,12 @@ __device__ __forceinline__ float silu_t(float x) { return x / (1.f + __expf(-x))
 //   w[strip][lane]  8 WGN packed weight tiles of 1 KiB exactly as in global memory
 //   x[group][pos]   activation rows in groups of 16; a row is 64 bytes = four
 //                   16-byte chunks, chunk c of row r stored at position
-//                   4 r + (c ^ ((r >> 1) & 3)) so that the operand reads of
-//                   eight consecutive rows fall into distinct banks.
+//                   4 r + (c ^ ((r >> 2) & 3)).  A 128-bit LDS read serves sixteen
+//                   lanes per cycle (256 bytes, 64 banks) -- lanes 0-7 together with
+//                   24-31, 8-15 with 16-23, the same in the upper half-wave
+//                   (measured) --, and with this swizzle the sixteen rows such a
+//                   set reads (rows 0-7 of one group, 8-15 of the next) fall into
+//                   sixteen distinct 16-byte phases.
 template <int WGN, int WGM, int WM>
 struct TiledStage {
   u32x4 w[8 * WGN][64];
@@ -47,7 +51,7 @@ __device__ __forceinline__ void tiled_read_frags(const TiledStage<WGN, WGM, WM>*
   for (int t = 0; t < WM; ++t) {
     const int r = l32 & 15;
     const int c = hi + 2 * kh;
-    f.x[t] = __builtin_bit_cast(bf16x8, st->x[(wm * WM + t) * 2 + (l32 >> 4)][4 * r + (c ^ ((r >> 1) & 3))]);
+    f.x[t] = __builtin_bit_cast(bf16x8, st->x[(wm * WM + t) * 2 + (l32 >> 4)][4 * r + (c ^ ((r >> 2) & 3))]);
   }
 }
 
@@ -106,7 +110,7 @@ __global__ __launch_bounds__(WGN* WGM * 64) void gemm_bf16_tiled_kernel(
 #pragma unroll
   for (int j = 0; j < XLOADS; ++j) {
     const int r = lane >> 2;
-    const int chunk = (lane & 3) ^ ((r >> 1) & 3);
+    const int chunk = (lane & 3) ^ ((r >> 2) & 3);
     int row = min(mrow0 + (wave * XLOADS + j) * 16 + r, M - 1);
     xsrc[j] = X + (int64_t)row * Kd + chunk * 8;
   }

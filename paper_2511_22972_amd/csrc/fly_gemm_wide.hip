@@ -54,8 +54,10 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
 
   // LDS: two activation blocks (the one being multiplied, the one being written).
   // One k-tile (32 wide) of 16 rows is 1 KiB: a row is four 16-byte pieces, piece c
-  // of row r at position 4 r + (c ^ ((r >> 1) & 3)), so that the operand reads of
-  // eight consecutive rows fall into distinct banks.
+  // of row r at position 4 r + (c ^ ((r >> 2) & 3)): a 128-bit LDS read serves
+  // sixteen lanes per cycle -- lanes 0-7 together with 24-31, 8-15 with 16-23, the same
+  // in the upper half-wave (measured) --, and the sixteen rows such a set reads (rows
+  // 0-7 of one 16-row group, 8-15 of the next) then fall into sixteen distinct phases.
   static_assert(RING % 2 == 0, "the register buffers of the activations alternate with the ring");
   __shared__ u32x4 xs[2][KC][2 * MT][64];
 
@@ -99,7 +101,7 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
 
   // Activation pieces this wave copies per chunk: piece f = wave + NWV i is k-tile
   // f / (2 MT), row group f % (2 MT); lane 4 r + c' fetches row r of the group,
-  // 16-byte piece c' ^ ((r >> 1) & 3), and the wave's 1 KiB is stored in lane
+  // 16-byte piece c' ^ ((r >> 2) & 3), and the wave's 1 KiB is stored in lane
   // order.  Rows past M are clamped to row M-1 (they feed output rows that are
   // never stored), k-tiles past the end to the last valid one (they meet zeroed
   // weight fragments).  A wave whose last piece index falls past the block loads
@@ -115,7 +117,7 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
     xkt[i] = fc / (2 * MT);
     xgrp[i] = fc % (2 * MT);
     const int r = lane >> 2;
-    const int piece = (lane & 3) ^ ((r >> 1) & 3);
+    const int piece = (lane & 3) ^ ((r >> 2) & 3);
     const int row = min(xgrp[i] * 16 + r, M - 1);
     xrow[i] = (const u32x4*)(X + (int64_t)row * Kd + piece * 8);
   }
@@ -158,7 +160,7 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
     const int c = hi + 2 * kh;
 #pragma unroll
     for (int t = 0; t < BT; ++t)
-      b[t] = __builtin_bit_cast(bf16x8, xs[stage][kt][2 * (t0 + t) + (l32 >> 4)][4 * r + (c ^ ((r >> 1) & 3))]);
+      b[t] = __builtin_bit_cast(bf16x8, xs[stage][kt][2 * (t0 + t) + (l32 >> 4)][4 * r + (c ^ ((r >> 2) & 3))]);
   };
   auto compute = [&](const u32x4 (&a)[CG][KC][2], int chunk, int stage) {
     bf16x8 b[2][BT];
