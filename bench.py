@@ -372,6 +372,21 @@ def main():
 
     ms = time_region(step, args.steps, args.warmup)
     graph_ms = graph_replay_ms(step, args.steps, args.warmup)
+    # The same step at temperature > 0: the target's tokens drawn instead of the argmax (a reading of
+    # ours, the paper prints no rule for its temperature-1 rows); its own outputs, the headline is the
+    # greedy step above.
+    out_s = fb.VerifyOutputs(cfg.batch, cfg.K)
+    sampled = torch.zeros(cfg.batch, cfg.K + 1, dtype=torch.int32, device="cuda")
+    call = [0]
+
+    def step_sampled():
+        call[0] += 1
+        fb.fly_verify_block_sampled(model, kv, tokens, row_scale, cfg.theta, cfg.window, cfg.seed, call[0],
+                                    sampled, out_s, ws)
+
+    sampled_ms = time_region(step_sampled, max(args.steps // 2, 3), 2)
+    step()  # leave the greedy step's rows in the cache and its outputs in `out`
+    torch.cuda.synchronize()
     accept_len = out.accept_len.cpu().numpy()
     s_total = int((accept_len + 1).sum())          # the paper's count: kept drafts + 1
     tokens_per_s = s_total / (ms * 1e-3)
@@ -466,6 +481,8 @@ def main():
         "lm_head": lm_head,
         "decode_loop": decode_loop_line(fb, cfg, desc, model, kv, row_scale),
         "model_drafted_loop": model_drafted_loop_line(fb, cfg, desc, model, kv, row_scale),
+        "sampled_step": {"ms_per_step": sampled_ms,
+                         "note": "fly_verify_block_sampled: target tokens drawn at the rows' temperatures (Gumbel-max fused into the LM head)"},
         "graph_replay": {"ms_per_step": graph_ms,
                          "note": "the same step captured once in a HIP graph and replayed; equal to the eager time when the device, not the host launch path, is the limit"},
     }
