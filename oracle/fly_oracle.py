@@ -495,13 +495,14 @@ def verify_block(tokens, embed: torch.Tensor, layers: Sequence[LayerWeights],
                  row_scale: Optional[torch.Tensor], *, n_q_heads: int, n_kv_heads: int,
                  head_dim: int, rope_theta: float, eps: float, theta: float, W: int,
                  storage: str = "f32", return_logits: bool = False,
-                 sample: Optional[Tuple[int, int]] = None) -> Dict[str, np.ndarray]:
+                 sample: Optional[Tuple[int, int]] = None, sample_row0: int = 0) -> Dict[str, np.ndarray]:
     """The whole verification step for B sequences (Sec. 2.1-2.2, Alg. 1 steps 2-4).
 
     With sample = (seed, offset) the target's tokens y_1..y_{K+1} are drawn from
-    softmax of the scaled logits (`sample_rows`, row m = b (K+1) + i) instead of
-    being their argmax, and the acceptance rule compares the drafts with the
-    drawn tokens; "sampled" and "sample_margin" are added to the result.
+    softmax of the scaled logits (`sample_rows`, row m = sample_row0 + b (K+1) + i)
+    instead of being their argmax, and the acceptance rule compares the drafts
+    with the drawn tokens; "sampled" and "sample_margin" are added to the result.
+    sample_row0 lets a block that is part of a larger batch draw what the batch draws.
 
     tokens [B, K+1] = (y_{-1}, draft_1..draft_K) per sequence.
     kv_prefix[layer] = (k [B, L, Hkv, hd], v [B, L, Hkv, hd]).
@@ -531,7 +532,8 @@ def verify_block(tokens, embed: torch.Tensor, layers: Sequence[LayerWeights],
     out = {k: v.reshape(B, R) for k, v in stats.items()}
     target = out["argmax"]
     if sample is not None:
-        drawn = sample_rows(logits.reshape(B * R, -1).numpy(), sample[0], sample[1])
+        drawn = sample_rows(logits.reshape(B * R, -1).numpy(), sample[0], sample[1],
+                            rows=sample_row0 + np.arange(B * R))
         out["sampled"] = drawn["token"].reshape(B, R)
         out["sample_margin"] = drawn["margin"].reshape(B, R)
         target = out["sampled"]
@@ -615,7 +617,7 @@ def decode_rounds(y0: Sequence[int], kv0: Sequence[Tuple[torch.Tensor, torch.Ten
                   w_lm: torch.Tensor, row_scale: Optional[torch.Tensor], *, rounds: int, K: int,
                   n_max: int, theta: float, W: int, n_q_heads: int, n_kv_heads: int,
                   head_dim: int, rope_theta: float, eps: float, storage: str = "f32",
-                  drafter=None) -> Dict:
+                  drafter=None, sample: Optional[Tuple[int, int]] = None, sample_row0: int = 0) -> Dict:
     """Algorithm 1's loop for ONE sequence, `rounds` rounds (no end-of-sequence
     token in the synthetic setting), with `pld_propose` as the drafter (or
     `drafter(y, K) -> (drafts, tag)` when given: Algorithm 1 takes any M_D).
@@ -628,17 +630,22 @@ def decode_rounds(y0: Sequence[int], kv0: Sequence[Tuple[torch.Tensor, torch.Ten
     target's own choice -- and the correction / bonus token becomes the next
     y_{-1}.  Returns the final sequence, s per round, tau = sum(s) / rounds
     (Eq. 12), the per-round statistics and the final cache.
+
+    With sample = (seed, offset) the target's tokens are drawn (see `verify_block`):
+    round r uses offset + r, rows sample_row0 .. sample_row0 + K of the draw.
     """
     y = [int(t) for t in y0]
     kv = [(k.clone(), v.clone()) for k, v in kv0]
     trace, loose, per_round = [], [], []
-    for _ in range(rounds):
+    for rnd in range(rounds):
         drafts, n = pld_propose(y, n_max, K) if drafter is None else drafter(y, K)
         tokens = np.asarray([[y[-1]] + drafts], dtype=np.int64)
         out = verify_block(tokens, embed, layers, g_final, w_lm,
                            [(k[None], v[None]) for k, v in kv], row_scale,
                            n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, head_dim=head_dim,
-                           rope_theta=rope_theta, eps=eps, theta=theta, W=W, storage=storage)
+                           rope_theta=rope_theta, eps=eps, theta=theta, W=W, storage=storage,
+                           sample=None if sample is None else (sample[0], sample[1] + rnd),
+                           sample_row0=sample_row0)
         a = int(out["accept_len"][0])
         s = a + 1
         y += drafts[:a] + [int(out["next_token"][0])]
@@ -648,5 +655,8 @@ def decode_rounds(y0: Sequence[int], kv0: Sequence[Tuple[torch.Tensor, torch.Ten
         loose.append(int(out["n_loose"][0]))
         per_round.append({"drafts": drafts, "ngram": n, "argmax": out["argmax"][0].copy(),
                           "h": out["h"][0].copy(), "margin": out["margin"][0].copy()})
+        if sample is not None:
+            per_round[-1]["sampled"] = out["sampled"][0].copy()
+            per_round[-1]["sample_margin"] = out["sample_margin"][0].copy()
     return {"y": y, "s": trace, "tau": sum(trace) / max(rounds, 1), "n_loose": loose,
             "rounds": per_round, "kv": kv}

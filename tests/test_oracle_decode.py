@@ -187,6 +187,42 @@ def incremental_greedy(model, cfg, y, K, first_pos):
     return out
 
 
+def test_loop_with_drawn_tokens(tiny):
+    """The loop at temperature > 0 (the drawn token takes the argmax's place, a reading of ours):
+    every round is the verification step with that round's draw on the state the rounds before
+    left; at a temperature near zero it is the greedy loop; and with the gate always strict every
+    emitted token is one the target drew."""
+    cfg, model, kv0, y0 = tiny
+    K, rounds = 4, 4
+    args = (model["embed"], model["layers"], model["g_final"], model["w_lm"])
+    hot = torch.full((K + 1,), 40.0)            # a gain on the tiny model's logits: a usable entropy range
+    res = O.decode_rounds(y0, kv0, *args, hot, rounds=rounds, K=K, n_max=3, theta=2.0, W=0,
+                          sample=(11, 100), sample_row0=2 * (K + 1), **model_args(cfg))
+    y, kv = list(y0), [(k.clone(), v.clone()) for k, v in kv0]
+    drew_other = 0
+    for r in range(rounds):
+        drafts = res["rounds"][r]["drafts"]
+        out = O.verify_block(np.asarray([[y[-1]] + drafts]), *args, [(k[None], v[None]) for k, v in kv], hot,
+                             theta=2.0, W=0, sample=(11, 100 + r), sample_row0=2 * (K + 1), **model_args(cfg))
+        assert np.array_equal(out["sampled"][0], res["rounds"][r]["sampled"])
+        s = int(out["accept_len"][0]) + 1
+        assert s == res["s"][r]
+        emitted = drafts[:s - 1] + [int(out["next_token"][0])]
+        assert emitted == [int(t) for t in out["sampled"][0][:s]]     # strict: only drawn tokens are emitted
+        drew_other += int((out["sampled"][0] != out["argmax"][0]).sum())
+        y += emitted
+        kv = [(torch.cat([k, nk[:s]]), torch.cat([v, nv[:s]])) for (k, v), (nk, nv) in zip(kv, out["new_kv"][0])]
+    assert y == res["y"] and drew_other > 0
+    other = O.decode_rounds(y0, kv0, *args, hot, rounds=rounds, K=K, n_max=3, theta=2.0, W=0,
+                            sample=(11, 101), sample_row0=2 * (K + 1), **model_args(cfg))
+    assert other["y"] != res["y"]                                       # the offset selects the draw
+    cold = torch.full((K + 1,), 1e6)
+    greedy = O.decode_rounds(y0, kv0, *args, cold, rounds=rounds, K=K, n_max=3, theta=0.3, W=1, **model_args(cfg))
+    drawn = O.decode_rounds(y0, kv0, *args, cold, rounds=rounds, K=K, n_max=3, theta=0.3, W=1,
+                            sample=(11, 100), **model_args(cfg))
+    assert drawn["y"] == greedy["y"] and drawn["s"] == greedy["s"]
+
+
 def test_model_drafter_equals_incremental_decoding():
     cfg = DRAFTER.replace(batch=1, kv_len=12)
     model = oracle_model(cfg)
