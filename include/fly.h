@@ -262,6 +262,18 @@ fly_status fly_decode_rounds(const fly_model_desc* desc, const fly_weights* w, c
                              void* workspace, size_t workspace_bytes, fly_stream stream);
 
 /*
+ * The same loop at temperature > 0: every round is fly_verify_block_sampled
+ * (which see, also for what this reading of the paper is), round r of the call
+ * drawing with offset + r; give consecutive calls of one run offsets `rounds`
+ * apart.  The drafter is unchanged.  Same workspace.
+ */
+fly_status fly_decode_rounds_sampled(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                                     const fly_sequences* seq, const float* row_scale, int32_t B, int32_t K,
+                                     float theta, int32_t W, int32_t ngram_max, int32_t rounds,
+                                     uint64_t seed, uint64_t offset, void* workspace,
+                                     size_t workspace_bytes, fly_stream stream);
+
+/*
  * Drafting with a draft model M_D (Algorithm 1 step 1 in the paper's own setting:
  * a small model of the target's family proposes, the target verifies).  For every
  * sequence b with n = ctx_len[b] tokens: the K tokens M_D emits greedily after

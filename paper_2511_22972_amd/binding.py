@@ -26,6 +26,7 @@ EXPORTS = [
     "fly_pld_draft", "fly_decode_workspace_bytes", "fly_decode_rounds",
     "fly_model_draft_workspace_bytes", "fly_model_draft", "fly_decode_model_workspace_bytes",
     "fly_decode_rounds_model", "fly_verify_block_sampled", "fly_lmhead_entropy_sample",
+    "fly_decode_rounds_sampled",
 ]
 
 
@@ -122,6 +123,10 @@ def _load() -> C.CDLL:
                                       C.POINTER(fly_kv_cache), C.POINTER(fly_sequences), C.c_void_p,
                                       C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_int32,
                                       C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.fly_decode_rounds_sampled.argtypes = [C.POINTER(fly_model_desc), C.POINTER(fly_weights),
+                                              C.POINTER(fly_kv_cache), C.POINTER(fly_sequences), C.c_void_p,
+                                              C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_int32,
+                                              C.c_uint64, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.fly_model_draft_workspace_bytes.argtypes = [C.POINTER(fly_model_desc), C.c_int32, C.c_int32, C.c_int32,
                                                     C.POINTER(C.c_size_t)]
     lib.fly_model_draft.argtypes = [C.POINTER(fly_model_desc), C.POINTER(fly_weights), C.POINTER(fly_kv_cache),
@@ -431,6 +436,19 @@ def fly_decode_rounds(model: PackedModel, kv: KVCache, seq: Sequences, row_scale
                                  _ptr(row_scale), kv.B, K, theta, W, ngram_max, rounds, _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream()),
            "fly_decode_rounds")
+    kv.max_kv_len += rounds * (K + 1)
+    seq.max_ctx_len += rounds * (K + 1)
+
+
+def fly_decode_rounds_sampled(model: PackedModel, kv: KVCache, seq: Sequences, row_scale: Optional[torch.Tensor],
+                              K: int, theta: float, W: int, ngram_max: int, rounds: int, seed: int, offset: int,
+                              workspace: torch.Tensor) -> None:
+    """The loop with drawn target tokens (round r draws with offset + r); moves the host-side bounds along."""
+    kvs, ss = kv.struct(), seq.struct()
+    _check(lib.fly_decode_rounds_sampled(C.byref(model.desc), C.byref(model.weights_c), C.byref(kvs), C.byref(ss),
+                                         _ptr(row_scale), kv.B, K, theta, W, ngram_max, rounds, seed, offset,
+                                         _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                         _stream()), "fly_decode_rounds_sampled")
     kv.max_kv_len += rounds * (K + 1)
     seq.max_ctx_len += rounds * (K + 1)
 

@@ -481,7 +481,7 @@ fly_status setup_draft(const fly_model_desc* desc, int B, int K, int max_kv_len,
 
 // Per-round buffers of the decode loop (behind the verification workspace).
 struct DecodeScratch {
-  int32_t *tokens, *accept_len, *next_token, *kv_len_out, *argmax, *n_loose;
+  int32_t *tokens, *accept_len, *next_token, *kv_len_out, *argmax, *n_loose, *sampled;
   float *h_norm, *p_top1;
   size_t bytes;
 };
@@ -501,6 +501,7 @@ void carve_decode(int B, int K, void* base, DecodeScratch* ds) {
   ds->argmax = (int32_t*)take(M * 4);
   ds->h_norm = (float*)take(M * 4);
   ds->p_top1 = (float*)take(M * 4);
+  ds->sampled = (int32_t*)take(M * 4);
   ds->bytes = off;
 }
 
@@ -806,10 +807,12 @@ fly_status fly_decode_workspace_bytes(const fly_model_desc* desc, int32_t B, int
   return FLY_OK;
 }
 
-fly_status fly_decode_rounds(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
-                             const fly_sequences* seq, const float* row_scale, int32_t B, int32_t K,
-                             float theta, int32_t W, int32_t ngram_max, int32_t rounds,
-                             void* workspace, size_t workspace_bytes, fly_stream stream) {
+// draw: NULL for the greedy loop, else {seed, offset}: round r draws the target's tokens with offset + r.
+static fly_status decode_rounds_entry(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                                      const fly_sequences* seq, const float* row_scale, int32_t B, int32_t K,
+                                      float theta, int32_t W, int32_t ngram_max, int32_t rounds,
+                                      const uint64_t* draw, void* workspace, size_t workspace_bytes,
+                                      fly_stream stream) {
   FLY_TRY(check_desc(desc));
   FLY_TRY(check_block(B, K));
   if (W < 0) return FLY_ERR_WINDOW;
@@ -844,12 +847,32 @@ fly_status fly_decode_rounds(const fly_model_desc* desc, const fly_weights* w, c
     int32_t* trace_row = seq->accept_trace ? seq->accept_trace + (int64_t)r * B : nullptr;
     HIP_TRY(launch_pld_draft(seq->ctx, seq->ctx_len, seq->ctx_capacity, B, K, ngram_max, ds.tokens,
                              ngram_row, st));
-    FLY_TRY(run_verify(desc, w, &kvr, ds.tokens, row_scale, B, K, theta, W, &out, ws, pl, st));
+    SampleRequest sr{draw ? draw[0] : 0, draw ? draw[1] + (uint64_t)r : 0, ds.sampled};
+    FLY_TRY(run_verify(desc, w, &kvr, ds.tokens, row_scale, B, K, theta, W, &out, ws, pl, st,
+                       draw ? &sr : nullptr));
     HIP_TRY(launch_roll_forward(seq->ctx, seq->ctx_len, seq->kv_len, seq->ctx_capacity, B, K, ds.tokens,
                                 ds.accept_len, ds.next_token, ds.kv_len_out, ds.n_loose,
                                 seq->accepted_total, seq->rounds_done, seq->loose_total, trace_row, st));
   }
   return FLY_OK;
+}
+
+fly_status fly_decode_rounds(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                             const fly_sequences* seq, const float* row_scale, int32_t B, int32_t K,
+                             float theta, int32_t W, int32_t ngram_max, int32_t rounds,
+                             void* workspace, size_t workspace_bytes, fly_stream stream) {
+  return decode_rounds_entry(desc, w, kv, seq, row_scale, B, K, theta, W, ngram_max, rounds, nullptr,
+                             workspace, workspace_bytes, stream);
+}
+
+fly_status fly_decode_rounds_sampled(const fly_model_desc* desc, const fly_weights* w, const fly_kv_cache* kv,
+                                     const fly_sequences* seq, const float* row_scale, int32_t B, int32_t K,
+                                     float theta, int32_t W, int32_t ngram_max, int32_t rounds,
+                                     uint64_t seed, uint64_t offset, void* workspace,
+                                     size_t workspace_bytes, fly_stream stream) {
+  const uint64_t draw[2] = {seed, offset};
+  return decode_rounds_entry(desc, w, kv, seq, row_scale, B, K, theta, W, ngram_max, rounds, draw, workspace,
+                             workspace_bytes, stream);
 }
 
 fly_status fly_model_draft_workspace_bytes(const fly_model_desc* desc, int32_t B, int32_t K,

@@ -220,6 +220,18 @@ def test_decode_argument_checks(fb):
     assert g(*args(wsb=out.value - 1)) == -9
 
 
+def test_decode_rounds_sampled_argument_checks(fb):
+    q = 4096
+    d = _desc(fb)
+    lw = (fb.fly_layer_weights * 2)(*[fb.fly_layer_weights(q, q, q, q, q, q)] * 2)
+    w = fb.fly_weights(q, lw, q, q)
+    karr = (C.c_void_p * 2)(q, q)
+    kv = fb.fly_kv_cache(karr, karr, q, 192, 128)
+    f = fb.lib.fly_decode_rounds_sampled
+    assert f(C.byref(d), C.byref(w), C.byref(kv), None, None, 1, 4, 0.3, 6, 3, 2, 7, 0, q, 1 << 30, None) == -1
+    assert f(C.byref(d), C.byref(w), C.byref(kv), None, None, 1, 70, 0.3, 6, 3, 2, 7, 0, q, 1 << 30, None) == -3
+
+
 def test_model_draft_argument_checks(fb):
     p = C.c_void_p(4096)
     d = _desc(fb)

@@ -51,7 +51,7 @@ def test_pld_draft_bit_exact():
         assert (got_n > 0).sum() > B // 2 and (got_n == 0).sum() > 0
 
 
-def run_gpu_loop(cfg, prompts, rounds, K, theta, W, n_max, row_scale=None):
+def run_gpu_loop(cfg, prompts, rounds, K, theta, W, n_max, row_scale=None, sample=None):
     fb = __import__("paper_2511_22972_amd.binding", fromlist=["x"])
     lens = [len(p) - 1 for p in prompts]
     cap = (max(lens) + rounds * (K + 1) + K + 1 + 63) // 64 * 64
@@ -59,18 +59,24 @@ def run_gpu_loop(cfg, prompts, rounds, K, theta, W, n_max, row_scale=None):
     seq = fb.Sequences(wl.kv, max(len(p) for p in prompts) + rounds * (K + 1) + 3, rounds)
     seq.set_sequences(prompts)
     ws = fb.alloc_workspace(fb.fly_decode_workspace_bytes(wl.desc, cfg.batch, K, max(lens) + rounds * (K + 1)))
-    fb.fly_decode_rounds(wl.model, wl.kv, seq, row_scale, K, theta, W, n_max, rounds, ws)
+    if sample is None:
+        fb.fly_decode_rounds(wl.model, wl.kv, seq, row_scale, K, theta, W, n_max, rounds, ws)
+    else:
+        fb.fly_decode_rounds_sampled(wl.model, wl.kv, seq, row_scale, K, theta, W, n_max, rounds, sample[0],
+                                     sample[1], ws)
     torch.cuda.synchronize()
     return wl, seq
 
 
-def oracle_loop(cfg, model, prompts, rounds, K, theta, W, n_max):
+def oracle_loop(cfg, model, prompts, rounds, K, theta, W, n_max, row_scale=None, sample=None):
     res = []
     for b, p in enumerate(prompts):
         L = len(p) - 1
         kv0 = [(k[b, :L], v[b, :L]) for k, v in model["kv_prefix"]]
+        rs = None if row_scale is None else row_scale.reshape(len(prompts), K + 1)[b]
         res.append(O.decode_rounds(p, kv0, model["embed"], model["layers"], model["g_final"], model["w_lm"],
-                                   None, rounds=rounds, K=K, n_max=n_max, theta=theta, W=W,
+                                   rs, rounds=rounds, K=K, n_max=n_max, theta=theta, W=W, sample=sample,
+                                   sample_row0=b * (K + 1),
                                    n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
                                    rope_theta=cfg.rope_theta, eps=cfg.rms_eps, storage=cfg.dtype))
     return res
@@ -82,7 +88,8 @@ def unambiguous_rounds(res, theta, tol=1e-3):
     the emitted token)."""
     for r, info in enumerate(res["rounds"]):
         s = res["s"][r]
-        amb = (info["margin"][:s] < tol) | (np.abs(info["h"][:s] - theta) < tol)
+        margin = info["sample_margin"] if "sample_margin" in info else info["margin"]
+        amb = (margin[:s] < tol) | (np.abs(info["h"][:s] - theta) < tol)
         if amb.any():
             return r
     return len(res["rounds"])
@@ -100,10 +107,11 @@ def make_prompts(cfg, lens, seed, period=None):
     return rows
 
 
-def check_loop(cfg, prompts, rounds, K, theta, W, n_max, kv_tol):
+def check_loop(cfg, prompts, rounds, K, theta, W, n_max, kv_tol, row_scale=None, sample=None):
     model = oracle_model(cfg)
-    wl, seq = run_gpu_loop(cfg, prompts, rounds, K, theta, W, n_max)
-    ora = oracle_loop(cfg, model, prompts, rounds, K, theta, W, n_max)
+    rs_dev = None if row_scale is None else row_scale.to("cuda", torch.float32).contiguous()
+    wl, seq = run_gpu_loop(cfg, prompts, rounds, K, theta, W, n_max, row_scale=rs_dev, sample=sample)
+    ora = oracle_loop(cfg, model, prompts, rounds, K, theta, W, n_max, row_scale=row_scale, sample=sample)
     trace = seq.accept_trace.cpu().numpy()
     ngram = seq.ngram_trace.cpu().numpy()
     ctx = seq.ctx.cpu().numpy()
@@ -159,6 +167,32 @@ def test_decode_rounds_bf16_small():
     prompts = make_prompts(cfg, [101, 60], seed=24, period=2)
     compared, kept, loose = check_loop(cfg, prompts, 10, K=4, theta=0.0, W=1, n_max=3, kv_tol=4e-2)
     assert compared >= 10 and kept > 0 and loose > 0
+
+
+def test_decode_rounds_sampled():
+    """The loop with drawn target tokens (temperature > 0): tokens, s per round and the cache against
+    the oracle's loop with the same draws (row b (K+1) + i of round r's offset), until a round that
+    hinges on a near tie of the perturbed logits."""
+    cfg = C1.replace(batch=3, kv_len=40)
+    prompts = make_prompts(cfg, [41, 23, 34], seed=25, period=5)
+    K, rounds = 4, 8
+    rs = torch.full((cfg.batch * (K + 1),), 40.0)   # a gain that spreads this tiny model's rows over the entropy range
+    compared, kept, _ = check_loop(cfg, prompts, rounds, K=K, theta=2.0, W=6, n_max=3, kv_tol=2e-4, row_scale=rs,
+                                   sample=(5, 1000))
+    assert compared >= rounds * 2
+    compared, kept, loose = check_loop(cfg, prompts, rounds, K=K, theta=0.0, W=1, n_max=3, kv_tol=2e-4,
+                                       row_scale=rs, sample=((9 << 32) | 5, (1 << 33) | 7))
+    assert compared >= rounds * 2 and kept > 0
+    # another offset, another continuation
+    wl_a, seq_a = run_gpu_loop(cfg, prompts, 4, K, 2.0, 6, 3, row_scale=rs.cuda(), sample=(5, 1000))
+    wl_b, seq_b = run_gpu_loop(cfg, prompts, 4, K, 2.0, 6, 3, row_scale=rs.cuda(), sample=(5, 2000))
+    assert not torch.equal(seq_a.ctx, seq_b.ctx)
+    bf = B16_SMALL.replace(batch=2, kv_len=100)
+    prompts = make_prompts(bf, [101, 60], seed=26, period=7)
+    rs = torch.full((bf.batch * (K + 1),), 6.0)
+    compared, _, _ = check_loop(bf, prompts, 6, K=K, theta=0.3, W=2, n_max=3, kv_tol=4e-2, row_scale=rs,
+                                sample=(3, 50))
+    assert compared >= 4
 
 
 def test_decode_rounds_limits():
