@@ -56,6 +56,29 @@ int splits_for(int nblocks, int nchunks) {
 // its 192-row workgroups beat the streaming kernel's nine 16-row tiles per wave).  Its workgroups cover 128, 192,
 // 256 or 384 rows: the shape that pads M least wins, the larger one on a tie (fewer
 // bytes staged per flop).
+// Split-K factor of the two kernels that take one workgroup per compute unit (LDS-tiled, wide).
+// `wgs` workgroups per split, `steps` pipeline steps along k.  The launch runs in
+// ceil(wgs * s / target) rounds of workgroups of steps / s steps each, and a round that is
+// not full takes as long as a full one: 288 workgroups on 256 units are two rounds.  Every
+// split also writes and re-reads a block of fp32 partial sums (about 5% per split,
+// measured at the 405B and 70B widths).  At least sixteen steps per split.
+static int pick_splits(int wgs, int steps) {
+  if (g_force_splits) return g_force_splits;
+  int best = 1;
+  double best_cost = 0.0;
+  for (int sp = 1; sp <= 16; ++sp) {
+    if (sp > 1 && steps / sp < 16) break;
+    const int per = (steps + sp - 1) / sp;
+    const int rounds = (wgs * sp + g_target_wgs - 1) / g_target_wgs;
+    const double cost = (double)rounds * per * (1.0 + 0.05 * sp);
+    if (sp == 1 || cost < best_cost) {
+      best = sp;
+      best_cost = cost;
+    }
+  }
+  return best;
+}
+
 GemmPlan plan_gemm_tiled(int M, int N, int Kd, bool allow_split, int forced) {
   GemmPlan p{1, 1, 1, 1, 3, 0};
   auto padded = [&](int shape) {
@@ -75,8 +98,8 @@ GemmPlan plan_gemm_tiled(int M, int N, int Kd, bool allow_split, int forced) {
     const int cols = gemm_bf16_tiled_cols(p.tiled);
     const int wgs = (N + cols - 1) / cols * p.mblocks;
     const int ktiles = Kd / 32;
-    int s = g_force_splits ? g_force_splits : (g_target_wgs + wgs / 2) / wgs;
-    int max_splits = ktiles / 16;  // at least sixteen k-steps per split
+    int s = pick_splits(wgs, ktiles);
+    int max_splits = ktiles / 16;  // at least sixteen k-steps per split (also for a forced factor)
     if (s > max_splits) s = max_splits;
     if (s > 16) s = 16;
     if (s < 1) s = 1;
@@ -96,7 +119,7 @@ GemmPlan plan_gemm_wide(int M, int N, int Kd, bool allow_split, int forced) {
     const int cols = gemm_bf16_wide_cols();
     const int wgs = (N + cols - 1) / cols;
     const int nchunks = (Kd / 32 + 1) / 2;
-    int s = g_force_splits ? g_force_splits : (g_target_wgs + wgs / 2) / wgs;
+    int s = pick_splits(wgs, nchunks);
     int max_splits = nchunks / 16;
     if (s > max_splits) s = max_splits;
     if (s > 16) s = 16;
