@@ -97,8 +97,9 @@ AttnPlan plan_attention(int B, int K, int Hq, int Hkv, int max_total_len) {
   int chunks = (max_total_len + ATT_KC - 1) / ATT_KC;
   if (chunks < 1) chunks = 1;
   // one workgroup per compute unit (the LDS ring allows no more), at least two
-  // stages per split
-  int want = g_attn_force_splits ? g_attn_force_splits : (256 + wgs - 1) / wgs;
+  // stages per split; the splits fill the 256 units without spilling into a second,
+  // nearly empty round of workgroups
+  int want = g_attn_force_splits ? g_attn_force_splits : (wgs >= 256 ? 1 : 256 / wgs);
   int maxsplit = (chunks + 1) / 2;
   if (maxsplit < 1) maxsplit = 1;
   int ns = want < maxsplit ? want : maxsplit;
