@@ -118,6 +118,34 @@ def test_down_projection_405b_width_is_reproducible(M):
         assert torch.equal(part[: splits * M * N], first), i
 
 
+@pytest.mark.parametrize("name", ["c3_70b", "c4_405b_slice", "p70b_k15_b16"])
+def test_layer_result_does_not_depend_on_stale_memory(name):
+    """One full-width layer with the workspace and the cache rows past the block filled with NaN
+    bytes, with huge finite values and with zeros: the result must be the same bits every time (no
+    kernel reads workspace it has not written in this call, nor cache rows that are not part of the
+    sequence)."""
+    cfg = synth.CONFIGS[name].replace(n_layers=1)
+    wl = GpuWorkload(cfg)
+    fb = wl.fb
+    x0 = synth.hash_normal(cfg.seed, 300, (cfg.M, cfg.d), 1.0, torch.float32, "cuda")
+
+    def run():
+        x = x0.clone()
+        fb.fly_decoder_layers(wl.model, wl.kv, x, 0, 1, cfg.batch, cfg.K, wl.ws)
+        torch.cuda.synchronize()
+        return x
+
+    ref = run()
+    assert torch.isfinite(ref).all()
+    end = cfg.kv_len + cfg.K + 1
+    for byte, value in ((0xFF, float("nan")), (0x7F, 3e38), (0x00, 0.0)):
+        wl.ws.fill_(byte)
+        assert torch.equal(run(), ref), ("workspace", byte)
+        wl.kv.k[0][:, :, end:, :] = value
+        wl.kv.v[0][:, :, :, end:] = value
+        assert torch.equal(run(), ref), ("cache padding", byte)
+
+
 def test_kernels_with_hand_counted_waits_are_reproducible():
     """The LDS-tiled GEMM and the attention kernel count the waits for their LDS-direct loads by hand.
     At sizes that miss every cache (1088 x 28672 activations, a 32768-key cache) twenty launches must
