@@ -107,6 +107,34 @@ def test_sample_bf16_tiled_kernel(fb, M, d, V):
         check_sample(*res)
 
 
+@pytest.mark.parametrize("M,d,V,dtype", [(5, 256, 8192, "f32"), (36, 1024, 4112, "bf16"), (136, 256, 2048 + 48, "bf16"),
+                                         (300, 544, 16 * 131, "bf16")])
+def test_lmhead_does_not_read_stale_workspace(fb, M, d, V, dtype):
+    """Every (row, part) record of the statistics and of the picks is written before the merge reads
+    it: the outputs do not change when the workspace is filled with NaN bytes or huge values first."""
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    hidden = synth.hash_normal(2, 201, (M, d), 4.0, tdt, "cuda")
+    w = synth.hash_normal(2, 202, (d, V), 0.02, tdt, "cuda")
+    code = fb.dtype_code(dtype)
+    wp = torch.empty(fb.fly_packed_weight_bytes(d, V, code) // w.element_size(), dtype=tdt, device="cuda")
+    fb.fly_pack_weight(w, wp, V)
+    ws = fb.alloc_workspace(fb.fly_lmhead_workspace_bytes(M, d, V, code))
+
+    def run():
+        outs = [torch.zeros(M, dtype=torch.int32, device="cuda") for _ in range(2)] + \
+               [torch.zeros(M, dtype=torch.float32, device="cuda") for _ in range(3)]
+        fb.fly_lmhead_entropy_sample(hidden, wp, None, V, 7, 3, outs[0], outs[1], outs[2], outs[3], outs[4], ws)
+        torch.cuda.synchronize()
+        return outs
+
+    ws.zero_()
+    ref = run()
+    for byte in (0xFF, 0x7F):
+        ws.fill_(byte)
+        for a, b in zip(run(), ref):
+            assert torch.equal(a, b), byte
+
+
 def test_seed_and_offset_select_the_draw(fb):
     M, d, V = 64, 64, 1024
     a, _, _ = sample_case(fb, M, d, V, "bf16", 5, 0, hidden_std=0.5)
