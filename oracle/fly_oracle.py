@@ -21,8 +21,12 @@ Pins (tests/test_oracle_*.py): closed forms of Eq. 5, the limit statements of
 the ablation section (theta=1, theta=0, W=0), the boundary rule j+W>K, brute
 force over all mismatch/gate patterns, scipy's logsumexp/entropy, torch's
 scaled_dot_product_attention, and the Hugging Face Llama implementation run
-in fp64 on a tiny model.  Free-running parity of the full forward at bf16
-depth is pinned only up to the stated logit tolerance (see `Numerics`).
+in fp64 on a tiny model.  The bf16 mode (`Numerics("bf16")`) is pinned by a
+two-key example worked by hand, by its invariance under integer octave shifts
+of the scores (and its change under half an octave), by exactness when every
+unnormalised probability is a power of two, by the one-rounding-per-term error
+bound against torch's softmax, and by the list of tensors it rounds, each of
+which matters (tests/test_oracle_bf16_pins.py).
 
   * prompt-lookup drafting     -- Sec. 2.3 names n-gram retrieval over the
                                   context as the parameter-free drafter and gives

@@ -330,7 +330,7 @@ __global__ __launch_bounds__(64) void accept_kernel(const int32_t* __restrict__ 
   const unsigned long long mm = __ballot(mism);  // bit l set: mismatch at position l+1
   bool rej = false;
   if (mism) {
-    if (strict || j + W > K) {
+    if (strict || W > K - j) {  // j + W > K, written so that no W overflows
       rej = true;
     } else if (W > 0) {
       // here j + W <= K <= 63, so both shifts are below 64

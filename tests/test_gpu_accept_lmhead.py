@@ -60,7 +60,8 @@ def test_accept_random_and_limits(fb):
         draft = np.where(rng.random((B, K)) < 0.8, target[:, :K], rng.integers(0, 128256, size=(B, K))).astype(np.int32)
         h = rng.random((B, K + 1)).astype(np.float32)
         h[::7, :] = np.float32(0.3)                       # equality at the gate defers
-        for theta, W in ((0.3, 6), (0.3, 0), (0.0, 0), (2.0, 6), (0.6, 2), (0.3, K), (0.3, 100)):
+        for theta, W in ((0.3, 6), (0.3, 0), (0.0, 0), (2.0, 6), (0.6, 2), (0.3, K), (0.3, 100),
+                         (0.3, 2 ** 31 - 1), (0.0, 2 ** 31 - 64)):
             ref = O.accept_block(draft, target, h, theta, W)
             acc, nxt, loose = run_accept(fb, draft, target, h, theta, W)
             assert np.array_equal(acc, ref["accept_len"]), (K, theta, W)
