@@ -69,3 +69,27 @@ def draft_chain(cfg: synth.VerifyConfig, model: Dict) -> np.ndarray:
         y_i = out["argmax"][:, i - 1]
         tokens[:, i] = np.where(u[:, i - 1] < cfg.p_match, y_i, alt[:, i - 1])
     return tokens
+
+
+def oracle_tail(cfg: synth.VerifyConfig, hidden: np.ndarray, tokens: np.ndarray, g_final: torch.Tensor,
+                w_lm: torch.Tensor, theta=None, W=None, sample=None) -> Dict:
+    """The end of the step on a GIVEN residual stream (Algorithm 1 steps 2-4 after the last layer):
+    final norm, LM head, row statistics (Eq. 1, Eq. 5) and the acceptance rule (Eqs. 2-11).
+    hidden [B*(K+1), d] is the residual stream after the last decoder layer -- in a teacher-forced
+    comparison the device's own."""
+    tokens = np.asarray(tokens)
+    B, R = tokens.shape
+    num = O.Numerics(cfg.dtype)
+    x = torch.from_numpy(np.asarray(hidden, dtype=np.float64)).view(B * R, -1)
+    xn = num.act(O.rmsnorm(x, g_final, cfg.rms_eps))
+    logits = O.lm_head_logits(xn, w_lm, row_scale(cfg))
+    out = {k: v.reshape(B, R) for k, v in O.decision_statistics(logits).items()}
+    target = out["argmax"]
+    if sample is not None:
+        drawn = O.sample_rows(logits.numpy(), sample[0], sample[1])
+        out["sampled"] = drawn["token"].reshape(B, R)
+        out["sample_margin"] = drawn["margin"].reshape(B, R)
+        target = out["sampled"]
+    out.update(O.accept_block(tokens[:, 1:], target, out["h"], cfg.theta if theta is None else theta,
+                              cfg.window if W is None else W))
+    return out

@@ -9,7 +9,7 @@ import torch
 import synth
 from oracle import fly_oracle as O
 from tests import helpers
-from tests.gpu_harness import GpuWorkload, ambiguous_rows, compare_verify
+from tests.gpu_harness import GpuWorkload, compare_tail, compare_verify
 
 pytestmark = pytest.mark.gpu
 
@@ -120,7 +120,7 @@ def test_verify_c1_tiny_fp32():
     """The tiny fp32 configuration end to end, free-running."""
     cfg = C1
     wl, tokens, gpu, ora = verify_case(cfg)
-    err = compare_verify(gpu, ora, cfg.theta, 1e-4, O.accept_block)
+    err = compare_verify(gpu, ora, cfg.theta, 1e-4, O.accept_block, tokens, cfg.window)
     # with W = 6 and K = 4 no window fits: the rule is exact-match decoding here
     std = np.array([O.s_standard(O.match_indicator(tokens[b, 1:], ora["argmax"][b])) for b in range(cfg.batch)])
     assert np.array_equal(ora["s"], std)
@@ -134,29 +134,29 @@ def test_verify_c1_with_fitting_windows(W):
     and a batch of sequences."""
     cfg = C1.replace(batch=6, logit_gain=12.0, window=W)
     wl, tokens, gpu, ora = verify_case(cfg)
-    compare_verify(gpu, ora, cfg.theta, 1e-4, O.accept_block)
+    compare_verify(gpu, ora, cfg.theta, 1e-4, O.accept_block, tokens, W, min_clean=3)
     assert ora["h"][:, :-1].min() < cfg.theta < ora["h"][:, :-1].max()
-    # the rule applied to the device's own statistics reproduces the device's decision
-    own = O.accept_block(tokens[:, 1:], gpu["argmax"], gpu["h_norm"], cfg.theta, W)
-    for k in ("accept_len", "next_token", "n_loose"):
-        assert np.array_equal(gpu[k], own[k])
 
 
 # 12 x 9 = 108 rows and 20 x 9 = 180 rows: the whole step through the GEMM kernel with 32-row tiles
 B16_ROWS108 = B16_SMALL.replace(name="bf16_rows108", batch=12, K=8, kv_len=70)
-# (seed chosen so that no bf16 rounding flip in the hidden state lands next to a 0.004 logit margin,
-# the free-running effect the fixed 1e-3 exclusion does not cover)
-B16_ROWS180 = B16_SMALL.replace(name="bf16_rows180", batch=20, K=8, kv_len=40, seed=B16_SMALL.seed + 2)
+B16_ROWS180 = B16_SMALL.replace(name="bf16_rows180", batch=20, K=8, kv_len=40)
 
 
 @pytest.mark.parametrize("cfg", [B16_SMALL, B16_WIDE, B16_ROWS108, B16_ROWS180])
 def test_verify_bf16_small(cfg):
+    """Two comparisons.  Free-running (the oracle runs its own layers): a bf16 rounding that falls
+    the other way in fp32 than in fp64 moves a hidden state, so the logits of the two sides differ
+    by up to the 2e-2 tolerance and the integer outputs are compared only where no margin is below
+    twice that.  Teacher-forced (the oracle's final norm, LM head, statistics and rule on the
+    device's own residual stream): the integer outputs must agree outside the 1e-3 exclusions."""
     cfg = cfg.replace(window=2)
     wl, tokens, gpu, ora = verify_case(cfg)
-    compare_verify(gpu, ora, cfg.theta, 2e-2, O.accept_block)
-    own = O.accept_block(tokens[:, 1:], gpu["argmax"], gpu["h_norm"], cfg.theta, cfg.window)
-    for k in ("accept_len", "next_token", "n_loose"):
-        assert np.array_equal(gpu[k], own[k])
+    compare_verify(gpu, ora, cfg.theta, 2e-2, O.accept_block, tokens, cfg.window, min_clean=0, int_tol=4e-2)
+    model = oracle_model_from_gpu(cfg)
+    tail = helpers.oracle_tail(cfg, gpu["hidden"], tokens, model["g_final"], model["w_lm"])
+    err = compare_tail(gpu, tail, cfg.theta, O.accept_block, tokens, cfg.window, min_clean=cfg.batch // 2)
+    print(cfg.name, "teacher-forced tail", err)
     assert np.array_equal(gpu["kv_len_out"], cfg.kv_len + gpu["accept_len"] + 1)
 
 
