@@ -1,12 +1,14 @@
 """Parity at the full sizes of the benchmark workloads, in the launch
 configuration bench.py times (same shapes, hence the same kernel plans).
 
-The oracle cannot run a whole 80-layer step in test time, and free-running
-bf16 agreement at depth is not pinned anyway (rounding flips decorrelate the two
-sides at full width).  So:
+Free-running bf16 agreement at depth means little (rounding flips decorrelate
+the two sides at full width), so the full-depth comparison is teacher-forced and
+lives in tests/test_gpu_fulldepth.py.  Here:
   * every stage is compared with the oracle at full width on seeded stage
     inputs (one decoder layer from a seeded residual stream; the LM head from
-    seeded hidden states, all rows or a sample of rows);
+    seeded hidden states, all rows; the 32768-key attention);
+  * the acceptance rule runs on the statistics of the 1088-row stress workload
+    with drafts drawn three ways;
   * the 8B shape runs free-running end to end at reduced depth with an
     oracle-built draft chain;
   * the full 80-layer 70B-shaped step is checked through properties that hold
@@ -68,7 +70,10 @@ def one_layer_case(cfg):
             assert torch.all(diff <= ref_t.abs() * 2.0 ** -7 + 1e-3), diff.max()
             assert (diff != 0).double().mean().item() < 0.02
     print(cfg.name, "one full-width layer: residual-stream error / rms(ref): max", worst_max, "rms", worst_rms)
-    assert worst_rms < 6e-3 and worst_max < 4e-2
+    # twice what the shapes of each width show (an fp32 evaluation of the same layer on the CPU with
+    # the same rounding points differs from the fp64 oracle by as much as the device does)
+    rms_tol, max_tol = {4096: (1.6e-3, 1.0e-2), 8192: (5e-3, 3.5e-2), 16384: (8.5e-3, 6e-2)}[cfg.d]
+    assert worst_rms < rms_tol and worst_max < max_tol
     return worst_max
 
 
