@@ -46,7 +46,8 @@ typedef enum {
   FLY_ERR_ALIGNMENT = -8,      /* a device pointer is not 16-byte aligned */
   FLY_ERR_WORKSPACE = -9,      /* workspace NULL or smaller than the query says */
   FLY_ERR_KV_CAPACITY = -10,   /* max_kv_len + K + 1 exceeds the cache capacity */
-  FLY_ERR_LAUNCH = -11         /* the HIP runtime refused a launch */
+  FLY_ERR_LAUNCH = -11,        /* the HIP runtime refused a launch */
+  FLY_ERR_STATIC_SCRATCH = -12 /* the request does not fit the library's static scratch array */
 } fly_status;
 
 typedef enum { FLY_F32 = 0, FLY_BF16 = 1 } fly_dtype;
@@ -347,6 +348,25 @@ fly_status fly_lmhead_entropy_sample(const void* hidden, const void* w_lm, const
                                      uint64_t offset, int32_t* sampled, int32_t* argmax, float* p_top1,
                                      float* h_norm, float* lse, void* workspace, size_t workspace_bytes,
                                      fly_stream stream);
+
+/*
+ * fly_lmhead_entropy_argmax for callers that cannot allocate device memory or
+ * pass a workspace: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments without the workspace, same
+ * kernels, same results bit for bit.  The partial row statistics live in a
+ * 16 MiB array that is part of the library's device image (every GPU the library
+ * runs on holds its own copy until the process ends); the call allocates and
+ * frees nothing.  A request whose fly_lmhead_workspace_bytes exceeds 16 MiB
+ * (about 170 rows at a 128256-token vocabulary) returns FLY_ERR_STATIC_SCRATCH
+ * with nothing launched.  All calls on one GPU share the array: calls that
+ * overlap on one GPU (different streams, different threads) race and must be
+ * serialised by the caller; calls on one stream are safe back to back.
+ */
+#define FLY_LMHEAD_STATIC_SCRATCH_BYTES (16u << 20)
+fly_status fly_lmhead_entropy_argmax_static(const void* hidden, const void* w_lm, const float* row_scale,
+                                            int32_t M, int32_t d, int32_t V, int32_t dtype,
+                                            int32_t* argmax, float* p_top1, float* h_norm, float* lse,
+                                            fly_stream stream);
 
 /*
  * FLy's loose acceptance rule (Eqs. 2-11; Algorithm 1 steps 3-4).

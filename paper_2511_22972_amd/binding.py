@@ -26,7 +26,7 @@ EXPORTS = [
     "fly_pld_draft", "fly_decode_workspace_bytes", "fly_decode_rounds",
     "fly_model_draft_workspace_bytes", "fly_model_draft", "fly_decode_model_workspace_bytes",
     "fly_decode_rounds_model", "fly_verify_block_sampled", "fly_lmhead_entropy_sample",
-    "fly_decode_rounds_sampled",
+    "fly_decode_rounds_sampled", "fly_lmhead_entropy_argmax_static",
 ]
 
 
@@ -106,6 +106,9 @@ def _load() -> C.CDLL:
     lib.fly_lmhead_entropy_argmax.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                               C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.fly_lmhead_entropy_argmax_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                                     C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                                     C.c_void_p, C.c_void_p, C.c_void_p]
     lib.fly_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float,
                                C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.fly_attention.argtypes = [C.POINTER(fly_model_desc), C.POINTER(fly_kv_cache), C.c_int32,
@@ -229,6 +232,17 @@ def fly_lmhead_entropy_argmax(hidden: torch.Tensor, w_lm_packed: torch.Tensor,
                                          _ptr(h_norm), _ptr(lse), _ptr(workspace),
                                          workspace.numel() * workspace.element_size(), _stream()),
            "fly_lmhead_entropy_argmax")
+
+
+def fly_lmhead_entropy_argmax_static(hidden: torch.Tensor, w_lm_packed: torch.Tensor,
+                                     row_scale: Optional[torch.Tensor], V: int, argmax: torch.Tensor,
+                                     p_top1: torch.Tensor, h_norm: torch.Tensor,
+                                     lse: Optional[torch.Tensor]) -> None:
+    M, d = hidden.shape
+    _check(lib.fly_lmhead_entropy_argmax_static(_ptr(hidden), _ptr(w_lm_packed), _ptr(row_scale), M, d, V,
+                                                dtype_code(hidden.dtype), _ptr(argmax), _ptr(p_top1),
+                                                _ptr(h_norm), _ptr(lse), _stream()),
+           "fly_lmhead_entropy_argmax_static")
 
 
 def fly_lmhead_entropy_sample(hidden: torch.Tensor, w_lm_packed: torch.Tensor,

@@ -528,6 +528,32 @@ void carve_decode(int B, int K, void* base, DecodeScratch* ds) {
   ds->bytes = off;
 }
 
+// --- the LM head for callers that cannot allocate ----------------------------
+// The partial row statistics of fly_lmhead_entropy_argmax_static live in this
+// file-scope device array instead of a caller's workspace.  In host code the
+// array's name is only a stand-in: its device address is looked up once per
+// device (hipGetSymbolAddress, with that device current) and kept; kernels,
+// copies and memsets get the looked-up pointer, never the name.
+#define FLY_STATIC_SCRATCH_BYTES (16u << 20)
+#define FLY_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char fly_static_scratch[FLY_STATIC_SCRATCH_BYTES];
+static void* g_static_scratch_ptr[FLY_MAX_DEVICES];  // per device; NULL = not looked up yet
+
+// Device address of the scratch array on the current device (no allocation).
+static fly_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= FLY_MAX_DEVICES) return FLY_ERR_LAUNCH;
+  void* p = __atomic_load_n(&g_static_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (p == nullptr) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(fly_static_scratch)) != hipSuccess || p == nullptr)
+      return FLY_ERR_LAUNCH;
+    // two threads racing here look up the same address: the store is idempotent
+    __atomic_store_n(&g_static_scratch_ptr[dev], p, __ATOMIC_RELEASE);
+  }
+  *out = p;
+  return FLY_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -546,6 +572,7 @@ const char* fly_strerror(fly_status s) {
     case FLY_ERR_WORKSPACE: return "workspace missing or too small";
     case FLY_ERR_KV_CAPACITY: return "max_kv_len + K + 1 exceeds the KV cache capacity";
     case FLY_ERR_LAUNCH: return "the HIP runtime refused a launch";
+    case FLY_ERR_STATIC_SCRATCH: return "the request needs more than the 16 MiB static scratch array";
   }
   return "unknown status";
 }
@@ -666,6 +693,24 @@ fly_status fly_lmhead_entropy_sample(const void* hidden, const void* w_lm, const
   SampleRequest sr{seed, offset, sampled};
   return lmhead_entry(hidden, w_lm, row_scale, M, d, V, dtype, argmax, p_top1, h_norm, lse, &sr, workspace,
                       workspace_bytes, stream);
+}
+
+fly_status fly_lmhead_entropy_argmax_static(const void* hidden, const void* w_lm, const float* row_scale,
+                                            int32_t M, int32_t d, int32_t V, int32_t dtype,
+                                            int32_t* argmax, float* p_top1, float* h_norm, float* lse,
+                                            fly_stream stream) {
+  // sizes first: nothing below touches the device before the request is known to fit
+  size_t need = 0;
+  FLY_TRY(fly_lmhead_workspace_bytes(M, d, V, dtype, &need));
+  if (need > FLY_STATIC_SCRATCH_BYTES) return FLY_ERR_STATIC_SCRATCH;
+  if (!hidden || !w_lm || !argmax || !p_top1 || !h_norm) return FLY_ERR_NULL_POINTER;
+  if (!aligned16(hidden) || !aligned16(w_lm)) return FLY_ERR_ALIGNMENT;
+  void* scratch = nullptr;
+  FLY_TRY(static_scratch(&scratch));
+  // every partial record the combine step reads is written by the GEMM of the same call, so the
+  // array needs no clearing between calls
+  return lmhead_entry(hidden, w_lm, row_scale, M, d, V, dtype, argmax, p_top1, h_norm, lse, nullptr, scratch,
+                      FLY_STATIC_SCRATCH_BYTES, stream);
 }
 
 fly_status fly_accept(const int32_t* draft, const int32_t* tgt_argmax, const float* h_norm, int32_t B,

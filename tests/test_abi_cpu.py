@@ -34,8 +34,8 @@ def test_every_declared_symbol_is_exported(fb):
 
 def test_strerror(fb):
     assert fb.strerror(0) == "ok"
-    seen = {fb.strerror(-i) for i in range(1, 12)}
-    assert len(seen) == 11 and "unknown status" not in seen
+    seen = {fb.strerror(-i) for i in range(1, 13)}
+    assert len(seen) == 12 and "unknown status" not in seen
     assert fb.strerror(-99) == "unknown status"
 
 
@@ -98,6 +98,20 @@ def test_lmhead_argument_checks(fb):
     assert f(p, p, None, 36, 8200, 128256, 1, p, p, p, None, p, need, None) == -2
     assert f(p, p, None, 36, 8192, 128256, 5, p, p, p, None, p, need, None) == -6
     assert f(p, p, None, 0, 8192, 128256, 1, p, p, p, None, p, need, None) == -2
+
+
+def test_static_scratch_lmhead_argument_checks(fb):
+    """The entry point without a workspace validates before it touches the device."""
+    p, odd = C.c_void_p(4096), C.c_void_p(4100)
+    f = fb.lib.fly_lmhead_entropy_argmax_static
+    assert f(p, p, None, 1088, 8192, 128256, fb.FLY_BF16, p, p, p, None, None) == -12   # 26 MB > 16 MiB
+    assert f(p, p, None, 0, 8192, 128256, fb.FLY_BF16, p, p, p, None, None) == -2
+    assert f(p, p, None, 36, 8192, 128250, fb.FLY_BF16, p, p, p, None, None) == -2
+    assert f(p, p, None, 36, 8192, 128256, 7, p, p, p, None, None) == -6
+    assert f(None, p, None, 36, 8192, 128256, fb.FLY_BF16, p, p, p, None, None) == -1
+    assert f(p, p, None, 36, 8192, 128256, fb.FLY_BF16, None, p, p, None, None) == -1
+    assert f(odd, p, None, 36, 8192, 128256, fb.FLY_BF16, p, p, p, None, None) == -8
+    assert "static scratch" in fb.strerror(-12)
 
 
 def test_sampled_entry_points_argument_checks(fb):
