@@ -31,9 +31,11 @@ DECODE_WARMUP = 2
 DECODE_NGRAM = 3
 MFMA_PEAK_TFLOPS = 2500.0   # dense bf16, published
 F32_PEAK_TFLOPS = 157.3     # fp32 vector / matrix, published
-# HBM bytes per launch of the dominant kernel from hardware counters (FETCH_SIZE and
-# WRITE_SIZE passes scaled by a 1 GiB copy; profiles/gateup_gemm_c3_70b_hbm_counters.md).
-MEASURED_TRAFFIC_BYTES = {"c3_70b": 946.6e6}
+# HBM bytes per launch of the dominant kernel.  NOT measured by this run: hardware counters cannot be
+# read from inside the process, so the figure comes from two `rocprofv3 --pmc` passes (FETCH_SIZE,
+# then WRITE_SIZE) over `bench.py --roofline-only`, each scaled by what the same counter reads for a
+# 1 GiB device copy; the summary with the commands is the file named here.
+MEASURED_TRAFFIC = {"c3_70b": {"bytes": 946.6e6, "source": "profiles/gateup_gemm_c3_70b_hbm_counters.md"}}
 # The paper's own figure where a preset is its setting (Table 3: Llama-3.1-70B target, K = 15,
 # batch 1, one MI355X).  Context only: its software stack, prefix length and precision are not
 # stated, so vs_baseline stays null.
@@ -177,18 +179,26 @@ def algorithmic_bytes(cfg):
             "total": per_layer * cfg.n_layers + lm + kvb}
 
 
-def time_region(fn, steps, warmup):
+def time_region(fn, steps, warmup, per_call=False):
+    """ms per call over `steps` calls after `warmup` untimed ones (events on the launch stream, one
+    region around all calls).  With per_call also the list of per-call times, from one more event
+    recorded after every call (the mean is still that of the whole region)."""
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    start = torch.cuda.Event(enable_timing=True)
-    end = torch.cuda.Event(enable_timing=True)
-    start.record()
-    for _ in range(steps):
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1 if per_call else 2)]
+    marks[0].record()
+    for i in range(steps):
         fn()
-    end.record()
+        if per_call:
+            marks[i + 1].record()
+    if not per_call:
+        marks[1].record()
     torch.cuda.synchronize()
-    return start.elapsed_time(end) / steps  # ms per call
+    mean = marks[0].elapsed_time(marks[-1]) / steps
+    if per_call:
+        return mean, [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
+    return mean
 
 
 def graph_replay_ms(step, steps, warmup):
@@ -221,6 +231,7 @@ def cpu_baseline(cfg, tokens_np, layers_sampled=1):
     f64 = lambda t: t.to("cpu", torch.float64)
     x0 = f64(synth.make_hidden(cfg, B * R, "cuda")).view(B, R, cfg.d)
     t_layer = 0.0
+    t_layer_1 = None
     for l in range(layers_sampled):
         w = helpers.oracle_layer_weights(cfg, l, "cuda")
         kp, vp = (f64(t) for t in synth.make_kv_prefix(cfg, l, "cuda"))
@@ -229,6 +240,15 @@ def cpu_baseline(cfg, tokens_np, layers_sampled=1):
             O.decoder_layer(x0[b], w, kp[b], vp[b], cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
                             cfg.rope_theta, cfg.rms_eps, num)
         t_layer += time.perf_counter() - t0
+        if l == 0:
+            # the same layer on one thread, ONE sequence of the batch (the sequences cost the same)
+            nthreads = torch.get_num_threads()
+            torch.set_num_threads(1)
+            t0 = time.perf_counter()
+            O.decoder_layer(x0[0], w, kp[0], vp[0], cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim,
+                            cfg.rope_theta, cfg.rms_eps, num)
+            t_layer_1 = (time.perf_counter() - t0) * B
+            torch.set_num_threads(nthreads)
         del w, kp, vp
     t_layer /= layers_sampled
     w_lm = f64(synth.make_weight(cfg, "w_lm", -1, "cuda"))
@@ -241,7 +261,7 @@ def cpu_baseline(cfg, tokens_np, layers_sampled=1):
                          cfg.theta, cfg.window)
     t_head = time.perf_counter() - t0
     total = cfg.n_layers * t_layer + t_head
-    return {"t_layer_s": t_layer, "t_head_s": t_head, "t_step_s": total,
+    return {"t_layer_s": t_layer, "t_layer_1thread_s": t_layer_1, "t_head_s": t_head, "t_step_s": total,
             "sample": f"{layers_sampled} of {cfg.n_layers} decoder layers + LM head + row statistics + "
                       f"acceptance for all {B * R} rows; step = n_layers x layer + head"}
 
@@ -370,7 +390,7 @@ def main():
     def step():
         fb.fly_verify_block(model, kv, tokens, row_scale, cfg.theta, cfg.window, out, ws)
 
-    ms = time_region(step, args.steps, args.warmup)
+    ms, per_step = time_region(step, args.steps, args.warmup, per_call=True)
     graph_ms = graph_replay_ms(step, args.steps, args.warmup)
     # The same step at temperature > 0: the target's tokens drawn instead of the argmax (a reading of
     # ours, the paper prints no rule for its temperature-1 rows); its own outputs, the headline is the
@@ -445,6 +465,28 @@ def main():
                "frac_of_mfma_peak": lm_flops / (lm_ms * 1e-3) / 1e12 / mfma_peak,
                "frac_of_hbm_peak": lm_bytes / (lm_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                "with_drawn_token_us": lms_ms * 1e3}
+    # The contraction regime in the same record: the LM head of the stress workload (64 sequences x 17
+    # positions = 1088 rows, same width and vocabulary, hence this model's own LM-head weights), where
+    # the GEMM is bound by the matrix cores -- the figure the >= 60% MFMA target is about.
+    lm_mfma = None
+    c5 = synth.CONFIGS["c5_stress"]
+    if cfg.dtype == "bf16" and cfg.d == c5.d and cfg.vocab == c5.vocab and cfg.M <= 256:
+        h5 = synth.make_hidden(c5, c5.M, "cuda")
+        rs5 = (1.0 / synth.make_row_temperature(c5, "cuda")).reshape(-1).contiguous()
+        ws5 = fb.alloc_workspace(fb.fly_lmhead_workspace_bytes(c5.M, c5.d, c5.vocab, desc.dtype))
+        o5 = fb.VerifyOutputs(c5.batch, c5.K)
+
+        def lmhead5():
+            fb.fly_lmhead_entropy_argmax(h5, model.w_lm, rs5, c5.vocab, o5.argmax.view(-1), o5.p_top1.view(-1),
+                                         o5.h_norm.view(-1), None, ws5)
+
+        ms5 = time_region(lmhead5, 10, 3)
+        fl5 = 2.0 * c5.M * c5.d * c5.vocab
+        lm_mfma = {"workload": "c5_stress LM head + fused row statistics (1088 rows x 8192 x 128256)",
+                   "bound": "mfma", "avg_launch_us": ms5 * 1e3, "flops_per_launch": fl5,
+                   "achieved": fl5 / (ms5 * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                   "frac": fl5 / (ms5 * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS}
+        del h5, ws5
     # Up to 256 rows every GEMM is bound by streaming its weights (the weight-
     # streaming kernels; 256 flop per weight byte is still below the ridge) and the
     # dominant kernel is gate/up.  Beyond that the GEMMs are dense contractions
@@ -462,13 +504,17 @@ def main():
         roofline = {"kernel": gu_kernel + " (gate/up projection + SwiGLU)",
                     "bound": "hbm", "achieved": gu_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": gu_gbs / HBM_PEAK_GBS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name) if not args.layers else None,
-                    "bytes_per_launch": gu_bytes, "avg_launch_us": gu_ms * 1e3}
+                    "traffic": None, "bytes_per_launch": gu_bytes, "avg_launch_us": gu_ms * 1e3}
+        if cfg.name in MEASURED_TRAFFIC and not args.layers:
+            roofline["traffic"] = MEASURED_TRAFFIC[cfg.name]["bytes"]
+            roofline["traffic_source"] = ("hardware counters of a separate profiler run, not of this run: "
+                                          + MEASURED_TRAFFIC[cfg.name]["source"])
 
     res = {
         "metric": "verified tokens/s (FLy verify step)", "value": tokens_per_s, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
-        "verify_step_us": ms * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "verify_step_us": ms * 1e3, "ms_per_step_median": float(np.median(per_step)),
+        "ms_per_step_min": float(np.min(per_step)), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "n_layers": cfg.n_layers, "d": cfg.d, "heads": f"{cfg.n_q_heads}q/{cfg.n_kv_heads}kv",
                    "ffn": cfg.ffn, "vocab": cfg.vocab, "batch": cfg.batch, "K": cfg.K,
@@ -479,6 +525,7 @@ def main():
         "roofline": roofline,
         "gate_up": {"avg_launch_us": gu_ms * 1e3, "achieved_GBps": gu_gbs, "achieved_TFLOPs": gu_flops / (gu_ms * 1e-3) / 1e12},
         "lm_head": lm_head,
+        "lm_head_mfma_regime": lm_mfma,
         "decode_loop": decode_loop_line(fb, cfg, desc, model, kv, row_scale),
         "model_drafted_loop": model_drafted_loop_line(fb, cfg, desc, model, kv, row_scale),
         "sampled_step": {"ms_per_step": sampled_ms,
@@ -492,7 +539,9 @@ def main():
         res["cpu_baseline"] = {"value": s_total / cb["t_step_s"], "unit": "tokens/s",
                                "cores": torch.get_num_threads(), "kind": "oracle", "sample": cb["sample"],
                                "oracle_step_s_extrapolated": cb["t_step_s"],
-                               "oracle_layer_s": cb["t_layer_s"], "oracle_head_s": cb["t_head_s"]}
+                               "oracle_layer_s": cb["t_layer_s"], "oracle_head_s": cb["t_head_s"],
+                               "oracle_layer_1thread_s": cb["t_layer_1thread_s"],
+                               "note_1thread": "the sampled layer on one thread: one sequence timed, times the batch"}
     print(json.dumps(res))
 
 
