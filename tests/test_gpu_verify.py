@@ -160,6 +160,42 @@ def test_verify_bf16_small(cfg):
     assert np.array_equal(gpu["kv_len_out"], cfg.kv_len + gpu["accept_len"] + 1)
 
 
+def test_verify_longest_block_and_empty_prefix():
+    """K = 63 (the longest block one wavefront holds), one sequence with an EMPTY cached prefix and
+    one with five cached rows, 128 rows in all; then the same block with the largest window an
+    int32 holds, which no draft position can fit: exact-match decoding."""
+    cfg = B16_SMALL.replace(name="bf16_k63", batch=2, K=63, kv_len=5, window=6, temperatures=(0.3, 1.0, 3.0))
+    kv_lens = [0, 5]
+    model = oracle_model_from_gpu(cfg)
+    prefix = ragged_prefix(model, kv_lens)
+    rng = np.random.default_rng(3)
+    tokens = rng.integers(0, cfg.vocab, size=(cfg.batch, cfg.K + 1)).astype(np.int32)
+    wl = GpuWorkload(cfg, kv_lens=kv_lens)
+    rs = helpers.row_scale(cfg)
+    first = wl.verify(tokens, rs)
+    # drafts that partly follow the device's own targets, so that long accepted prefixes occur
+    keep = rng.random((cfg.batch, cfg.K)) < 0.9
+    tokens[:, 1:] = np.where(keep, first["argmax"][:, :-1], tokens[:, 1:])
+    gpu = wl.verify(tokens, rs)
+    ora = {k: [] for k in ("argmax", "margin", "lse", "h", "p_top1", "accept_len", "next_token", "n_loose")}
+    for b, L in enumerate(kv_lens):        # the oracle takes one prefix length per call
+        out = O.verify_block(tokens[b:b + 1], model["embed"], model["layers"], model["g_final"], model["w_lm"],
+                             [(k[b][None], v[b][None]) for k, v in prefix], rs.view(cfg.batch, -1)[b],
+                             n_q_heads=cfg.n_q_heads, n_kv_heads=cfg.n_kv_heads, head_dim=cfg.head_dim,
+                             rope_theta=cfg.rope_theta, eps=cfg.rms_eps, theta=cfg.theta, W=cfg.window,
+                             storage=cfg.dtype)
+        for k in ora:
+            ora[k].append(out[k])
+    ora = {k: np.concatenate(v) for k, v in ora.items()}
+    compare_verify(gpu, ora, cfg.theta, 2e-2, O.accept_block, tokens, cfg.window, min_clean=0, int_tol=4e-2)
+    tail = helpers.oracle_tail(cfg, gpu["hidden"], tokens, model["g_final"], model["w_lm"])
+    compare_tail(gpu, tail, cfg.theta, O.accept_block, tokens, cfg.window, min_clean=1)
+    assert np.array_equal(gpu["kv_len_out"], np.asarray(kv_lens) + gpu["accept_len"] + 1)
+    huge = wl.verify(tokens, rs, W=2 ** 31 - 1)
+    std = np.array([O.s_standard(O.match_indicator(tokens[b, 1:], huge["argmax"][b])) for b in range(cfg.batch)])
+    assert np.array_equal(huge["accept_len"] + 1, std) and not huge["n_loose"].any()
+
+
 def test_verify_limits_on_device():
     """theta > 1 gives exact-match decoding; theta = 0 with W = 0 accepts everything."""
     cfg = B16_SMALL.replace(batch=4, K=8)
