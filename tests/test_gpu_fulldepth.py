@@ -36,7 +36,7 @@ import torch
 import synth
 from oracle import fly_oracle as O
 from tests import helpers
-from tests.gpu_harness import GpuWorkload, compare_tail
+from tests.gpu_harness import GpuWorkload, check_own_rule, compare_tail
 
 pytestmark = pytest.mark.gpu
 
@@ -141,6 +141,21 @@ def teacher_forced_depth(cfg, capsys, layer_rms_tol, layer_max_tol, min_clean, f
         say(f"[{cfg.name}] the same with temperatures {mixed}: {merr}; accepted lengths "
             f"{mgpu['accept_len'].tolist()}, kept mismatches {mgpu['n_loose'].tolist()}; "
             f"h range {mtail['h'].min():.3f} .. {mtail['h'].max():.3f}")
+    else:
+        mcfg, mtail = cfg, tail
+    # shorter windows fit more draft positions, so mismatching drafts are kept more often: the rule
+    # on the same oracle statistics against one more device pass per window
+    for W in (0, 1, 2):
+        wgpu = wl.verify(tokens, helpers.row_scale(mcfg), W=W, want_hidden=False)
+        check_own_rule(wgpu, tokens, cfg.theta, W, O.accept_block)
+        want = O.accept_block(tokens[:, 1:], mtail["argmax"], mtail["h"], cfg.theta, W)
+        amb = (mtail["margin"] < 1e-3) | (np.abs(mtail["h"] - cfg.theta) < 1e-3)
+        clean = ~amb.any(axis=1)
+        assert clean.sum() >= min_clean
+        for k in ("accept_len", "next_token", "n_loose"):
+            assert np.array_equal(wgpu[k][clean], want[k][clean]), (cfg.name, "W", W, k)
+        say(f"[{cfg.name}] W = {W}: accepted lengths {wgpu['accept_len'].tolist()}, kept mismatches "
+            f"{wgpu['n_loose'].tolist()} (oracle {want['n_loose'].tolist()})")
 
     if free_running:
         free = helpers.oracle_tail(cfg, x_free.view(B * R, d).numpy(), tokens, g_final, w_lm)
