@@ -88,7 +88,14 @@ def test_layers_f32_tiny():
     check_appended_kv(wl, cfg, kv_lens, new_kv, 1e-5)
 
 
-@pytest.mark.parametrize("cfg,kv_lens", [(B16_SMALL, [150, 64]), (B16_WIDE, [300, 1, 129])])
+# d = 1056 is 33 k-steps and F = 1184 is 37: ragged last chunks in every projection, 48 rows
+B16_RAGGED_K = synth.CONFIGS["c2_8b"].replace(
+    name="bf16_ragged_k", n_layers=2, d=1056, n_q_heads=6, n_kv_heads=3, ffn=1184, vocab=2048,
+    batch=3, K=15, kv_len=100, weight_std=0.03)
+
+
+@pytest.mark.parametrize("cfg,kv_lens", [(B16_SMALL, [150, 64]), (B16_WIDE, [300, 1, 129]),
+                                         (B16_RAGGED_K, [100, 0, 37]), (B16_SMALL.replace(batch=1, K=1, kv_len=9), [9])])
 def test_layers_bf16(cfg, kv_lens):
     wl, got, ref, new_kv = run_layers_case(cfg, kv_lens)
     # residual stream is fp32 on the device; both sides round the same tensors to bf16
@@ -143,7 +150,7 @@ B16_ROWS108 = B16_SMALL.replace(name="bf16_rows108", batch=12, K=8, kv_len=70)
 B16_ROWS180 = B16_SMALL.replace(name="bf16_rows180", batch=20, K=8, kv_len=40)
 
 
-@pytest.mark.parametrize("cfg", [B16_SMALL, B16_WIDE, B16_ROWS108, B16_ROWS180])
+@pytest.mark.parametrize("cfg", [B16_SMALL, B16_WIDE, B16_RAGGED_K, B16_ROWS108, B16_ROWS180])
 def test_verify_bf16_small(cfg):
     """Two comparisons.  Free-running (the oracle runs its own layers): a bf16 rounding that falls
     the other way in fp32 than in fp64 moves a hidden state, so the logits of the two sides differ
