@@ -354,6 +354,10 @@ def main():
     ap.add_argument("--workload", default="c3_70b", choices=sorted(synth.CONFIGS))
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--step-only", action="store_true",
+                    help="only the timed step and the isolated gate/up and LM-head launches: no graph replay, "
+                         "no drawn-token step, no decode loops (for profiler runs, where every extra launch "
+                         "mixes into the per-kernel averages)")
     ap.add_argument("--kernel", default="auto", choices=["auto", "gateup", "lmhead", "attention"],
                     help="with --roofline-only: which kernel to launch alone (auto = the dominant one)")
     ap.add_argument("--roofline-only", action="store_true",
@@ -391,7 +395,7 @@ def main():
         fb.fly_verify_block(model, kv, tokens, row_scale, cfg.theta, cfg.window, out, ws)
 
     ms, per_step = time_region(step, args.steps, args.warmup, per_call=True)
-    graph_ms = graph_replay_ms(step, args.steps, args.warmup)
+    graph_ms = None if args.step_only else graph_replay_ms(step, args.steps, args.warmup)
     # The same step at temperature > 0: the target's tokens drawn instead of the argmax (a reading of
     # ours, the paper prints no rule for its temperature-1 rows); its own outputs, the headline is the
     # greedy step above.
@@ -404,7 +408,7 @@ def main():
         fb.fly_verify_block_sampled(model, kv, tokens, row_scale, cfg.theta, cfg.window, cfg.seed, call[0],
                                     sampled, out_s, ws)
 
-    sampled_ms = time_region(step_sampled, max(args.steps // 2, 3), 2)
+    sampled_ms = None if args.step_only else time_region(step_sampled, max(args.steps // 2, 3), 2)
     step()  # leave the greedy step's rows in the cache and its outputs in `out`
     torch.cuda.synchronize()
     accept_len = out.accept_len.cpu().numpy()
@@ -456,7 +460,7 @@ def main():
                                      lm_out.argmax.view(-1), lm_out.p_top1.view(-1), lm_out.h_norm.view(-1),
                                      None, lm_ws)
 
-    lms_ms = time_region(lmhead_sampled, max(args.steps, 20), 4)
+    lms_ms = float("nan") if args.step_only else time_region(lmhead_sampled, max(args.steps, 20), 4)
     lm_bytes = cfg.d * cfg.vocab * es + cfg.M * cfg.d * es
     lm_flops = 2.0 * cfg.M * cfg.d * cfg.vocab
     mfma_peak = MFMA_PEAK_TFLOPS if cfg.dtype == "bf16" else F32_PEAK_TFLOPS
@@ -470,7 +474,7 @@ def main():
     # the GEMM is bound by the matrix cores -- the figure the >= 60% MFMA target is about.
     lm_mfma = None
     c5 = synth.CONFIGS["c5_stress"]
-    if cfg.dtype == "bf16" and cfg.d == c5.d and cfg.vocab == c5.vocab and cfg.M <= 256:
+    if cfg.dtype == "bf16" and cfg.d == c5.d and cfg.vocab == c5.vocab and cfg.M <= 256 and not args.step_only:
         h5 = synth.make_hidden(c5, c5.M, "cuda")
         rs5 = (1.0 / synth.make_row_temperature(c5, "cuda")).reshape(-1).contiguous()
         ws5 = fb.alloc_workspace(fb.fly_lmhead_workspace_bytes(c5.M, c5.d, c5.vocab, desc.dtype))
@@ -526,8 +530,8 @@ def main():
         "gate_up": {"avg_launch_us": gu_ms * 1e3, "achieved_GBps": gu_gbs, "achieved_TFLOPs": gu_flops / (gu_ms * 1e-3) / 1e12},
         "lm_head": lm_head,
         "lm_head_mfma_regime": lm_mfma,
-        "decode_loop": decode_loop_line(fb, cfg, desc, model, kv, row_scale),
-        "model_drafted_loop": model_drafted_loop_line(fb, cfg, desc, model, kv, row_scale),
+        "decode_loop": None if args.step_only else decode_loop_line(fb, cfg, desc, model, kv, row_scale),
+        "model_drafted_loop": None if args.step_only else model_drafted_loop_line(fb, cfg, desc, model, kv, row_scale),
         "sampled_step": {"ms_per_step": sampled_ms,
                          "note": "fly_verify_block_sampled: target tokens drawn at the rows' temperatures (Gumbel-max fused into the LM head)"},
         "graph_replay": {"ms_per_step": graph_ms,
