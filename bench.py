@@ -541,7 +541,8 @@ def main():
         torch.cuda.synchronize()
         cb = cpu_baseline(cfg, tokens.cpu().numpy())
         res["cpu_baseline"] = {"value": s_total / cb["t_step_s"], "unit": "tokens/s",
-                               "cores": torch.get_num_threads(), "kind": "oracle", "sample": cb["sample"],
+                               "cores": torch.get_num_threads(), "host_logical_cpus": os.cpu_count(),
+                               "kind": "oracle", "sample": cb["sample"],
                                "oracle_step_s_extrapolated": cb["t_step_s"],
                                "oracle_layer_s": cb["t_layer_s"], "oracle_head_s": cb["t_head_s"],
                                "oracle_layer_1thread_s": cb["t_layer_1thread_s"],
