@@ -19,7 +19,8 @@
  *   - Arguments are validated on the host before anything is enqueued; on an
  *     error nothing has been launched.
  *   - M = B*(K+1) rows; row m = b*(K+1) + i is position i of sequence b and
- *     sits at absolute position kv_len[b] + i.
+ *     sits at absolute position kv_len[b] + i.  1 <= B <= 65536 and 1 <= K <= 63
+ *     (FLY_ERR_BAD_SHAPE / FLY_ERR_K_RANGE otherwise).
  *   - dtype FLY_F32: weights, KV cache and activations are fp32.
  *     dtype FLY_BF16: weights, KV cache and GEMM operands are bf16, the
  *     residual stream, accumulators and all statistics are fp32.
@@ -124,7 +125,8 @@ typedef struct {
 const char* fly_strerror(fly_status s);
 
 /*
- * Launch-shape knobs for experiments (process-wide, not thread-safe):
+ * Launch-shape knobs for experiments (process-wide; a change made while another thread plans a
+ * call is seen by that call or by the next):
  *   "gemm_nt"      16-column weight tiles per wavefront: 1, 2, 4; 0 = automatic
  *   "gemm_splits"  split-K factor of the projections: 1..16; 0 = automatic
  *   "gemm_mt_max"  most 16-row activation tiles one workgroup holds: 5 or 9 (default 9)

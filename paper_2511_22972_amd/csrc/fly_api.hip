@@ -1,6 +1,7 @@
 // C ABI of the FLy verification step: argument validation, workspace
 // planning and the launch sequence.  See include/fly.h for the contract.
 #include <math.h>
+#include <atomic>
 #include <stdlib.h>
 #include <string.h>
 
@@ -8,13 +9,14 @@
 
 namespace {
 
-// --- tuning knobs (0 = automatic); set through fly_set_tuning ---------------
-int g_force_nt = 0;
-int g_force_splits = 0;
-int g_target_wgs = 256;
-int g_mt_max = 9;
-int g_tiled = 0;  // 0 automatic, 1 never, 2, 3, 4 or 6: always, with that workgroup shape
-int g_wide = 0;   // 0 automatic (81..256 rows), 1 never, 3, 4, 5, 6 or 8: always, with that many 32-row tiles
+// --- tuning knobs (0 = automatic); set through fly_set_tuning.  Atomics: a change from one thread
+// while another plans a call is seen by that call or by the next, never torn. ---------------
+std::atomic<int> g_force_nt{0};
+std::atomic<int> g_force_splits{0};
+std::atomic<int> g_target_wgs{256};
+std::atomic<int> g_mt_max{9};
+std::atomic<int> g_tiled{0};  // 0 automatic, 1 never, 2, 3, 4 or 6: always, with that workgroup shape
+std::atomic<int> g_wide{0};   // 0 automatic (81..256 rows), 1 never, 3, 4, 5, 6 or 8: always, with that many 32-row tiles
 
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 
@@ -135,14 +137,14 @@ GemmPlan plan_gemm(int M, int N, int Kd, bool allow_split, bool need_even_nt) {
   // (256 rows) shapes: up to 80 rows the kernel with 16-row tiles wins, from 81 to 256 rows the
   // wide kernel wins or ties for every GEMM of the layer and for the LM head.
   if (g_wide >= 3 || (g_wide == 0 && g_tiled < 2 && M > 80 && M <= 256))
-    return plan_gemm_wide(M, N, Kd, allow_split, g_wide >= 3 ? g_wide : 0);
+    return plan_gemm_wide(M, N, Kd, allow_split, g_wide >= 3 ? g_wide.load() : 0);
   if (g_tiled >= 2 || (g_tiled == 0 && M > 128)) return plan_gemm_tiled(M, N, Kd, allow_split, g_tiled);
   GemmPlan p;
   p.tiled = 0;
   p.wide = 0;
   const int rows_max = g_mt_max * 16;
   p.mblocks = (M + rows_max - 1) / rows_max;
-  p.mt = p.mblocks > 1 ? g_mt_max : pick_mt(M);
+  p.mt = p.mblocks > 1 ? g_mt_max.load() : pick_mt(M);
   const int ntiles = N / 16;
   const int nchunks = (Kd / 32 + 3) / 4;
   const int nt_max = 4;
@@ -160,7 +162,7 @@ GemmPlan plan_gemm(int M, int N, int Kd, bool allow_split, bool need_even_nt) {
   if (need_even_nt && nt < 2) nt = 2;
   p.nt = nt;
   p.splits = 1;
-  if (allow_split) p.splits = g_force_splits ? g_force_splits : splits_for(blocks(nt), nchunks);
+  if (allow_split) p.splits = g_force_splits ? g_force_splits.load() : splits_for(blocks(nt), nchunks);
   if (allow_split && g_force_splits) {
     int cps = (nchunks + p.splits - 1) / p.splits;
     p.splits = (nchunks + cps - 1) / cps;
@@ -212,7 +214,8 @@ fly_status check_desc(const fly_model_desc* desc) {
 }
 
 fly_status check_block(int B, int K) {
-  if (B < 1 || B > (1 << 20)) return FLY_ERR_BAD_SHAPE;
+  // at most 65536 sequences: row and table indices (B * (K+1) * head_dim / 2 ...) stay far inside int32
+  if (B < 1 || B > (1 << 16)) return FLY_ERR_BAD_SHAPE;
   if (K < 1 || K > 63) return FLY_ERR_K_RANGE;
   return FLY_OK;
 }

@@ -80,8 +80,8 @@ __device__ __forceinline__ void att_global_to_lds16(const void* gptr, const void
   __builtin_amdgcn_sched_barrier(0);    \
   asm volatile("" ::: "memory")
 
-int g_attn_force_splits = 0;  // tuning knobs (0 = automatic)
-int g_attn_force_block_tiles = 0;
+std::atomic<int> g_attn_force_splits{0};  // tuning knobs (0 = automatic)
+std::atomic<int> g_attn_force_block_tiles{0};
 
 AttnPlan plan_attention(int B, int K, int Hq, int Hkv, int max_total_len) {
   AttnPlan p;
@@ -90,7 +90,7 @@ AttnPlan plan_attention(int B, int K, int Hq, int Hkv, int max_total_len) {
   int qt = (R + 31) / 32;  // 32-row query tiles
   // A workgroup holds up to eight tiles; more rows are divided evenly over
   // several query blocks.  Up to four tiles take the key-split kernel.
-  int per_block = g_attn_force_block_tiles ? g_attn_force_block_tiles : 8;
+  int per_block = g_attn_force_block_tiles ? g_attn_force_block_tiles.load() : 8;
   p.qblocks = (qt + per_block - 1) / per_block;
   p.block_tiles = (qt + p.qblocks - 1) / p.qblocks;
   int wgs = B * Hkv * p.qblocks;
@@ -99,7 +99,7 @@ AttnPlan plan_attention(int B, int K, int Hq, int Hkv, int max_total_len) {
   // one workgroup per compute unit (the LDS ring allows no more), at least two
   // stages per split; the splits fill the 256 units without spilling into a second,
   // nearly empty round of workgroups
-  int want = g_attn_force_splits ? g_attn_force_splits : (wgs >= 256 ? 1 : 256 / wgs);
+  int want = g_attn_force_splits ? g_attn_force_splits.load() : (wgs >= 256 ? 1 : 256 / wgs);
   int maxsplit = (chunks + 1) / 2;
   if (maxsplit < 1) maxsplit = 1;
   int ns = want < maxsplit ? want : maxsplit;

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include "../../include/fly.h"
 
 typedef uint16_t bf16_t;  // raw bf16 bits
@@ -322,7 +323,7 @@ struct AttnPlan {
                    // rows are divided over several workgroups that stream the same keys
   int block_tiles; // 32-row tiles per query block (1..8)
 };
-extern int g_attn_force_splits, g_attn_force_block_tiles;
+extern std::atomic<int> g_attn_force_splits, g_attn_force_block_tiles;
 AttnPlan plan_attention(int B, int K, int Hq, int Hkv, int max_total_len);
 size_t attention_workspace_floats(int B, int K, int Hq, int Hkv, int hd, const AttnPlan& p);
 hipError_t launch_attention_bf16(const bf16_t* q, const bf16_t* kcache, const bf16_t* vcache,

@@ -77,6 +77,7 @@ def test_accept_argument_checks(fb):
     assert f(None, p, p, 1, 4, 0.3, 6, p, p, None, None) == -1
     assert f(p, p, p, 1, 4, 0.3, 6, None, p, None, None) == -1
     assert f(p, p, p, 0, 4, 0.3, 6, p, p, None, None) == -2
+    assert f(p, p, p, 65537, 4, 0.3, 6, p, p, None, None) == -2
     assert f(p, p, p, 1, 0, 0.3, 6, p, p, None, None) == -3
     assert f(p, p, p, 1, 64, 0.3, 6, p, p, None, None) == -3
     assert f(p, p, p, 1, 4, 0.3, -1, p, p, None, None) == -4
