@@ -9,7 +9,9 @@ oracle is fed the DEVICE's own intermediate results, stage by stage:
   * the device runs the whole model one layer at a time (fly_decoder_layers
     (l, l+1)); for every layer the oracle's decoder_layer gets the device's
     layer input and its output is compared with the device's layer output
-    (residual stream relative to its rms; the rows appended to the KV cache);
+    (residual stream relative to its rms, and the difference must be spread like
+    rounding noise: no row and no block of 128 columns carries much more of it
+    than the rest; the rows appended to the KV cache);
   * the chained per-layer run must equal the one-call step bit for bit;
   * the oracle's final norm, LM head, row statistics (Eq. 1, Eq. 5) and
     acceptance rule (Eqs. 2-11; Algorithm 1 steps 2-4) are applied to the
@@ -75,7 +77,7 @@ def teacher_forced_depth(cfg, capsys, layer_rms_tol, layer_max_tol, min_clean, f
     x = embed[torch.as_tensor(tokens.reshape(-1).astype(np.int64), device="cuda")].float().contiguous()
     x_free = x.cpu().double().view(B, R, d).clone() if free_running else None
     num = O.Numerics(cfg.dtype)
-    worst = {"rms": 0.0, "max": 0.0, "kv_flips": 0.0, "free_rms": 0.0}
+    worst = {"rms": 0.0, "max": 0.0, "kv_flips": 0.0, "free_rms": 0.0, "row": 0.0, "blk": 0.0}
     for l in range(cfg.n_layers):
         x_in = x.cpu().double().view(B, R, d)
         fb.fly_decoder_layers(wl.model, wl.kv, x, l, l + 1, B, K, wl.ws)
@@ -93,6 +95,17 @@ def teacher_forced_depth(cfg, capsys, layer_rms_tol, layer_max_tol, min_clean, f
             worst["rms"], worst["max"] = max(worst["rms"], rel_rms), max(worst["max"], rel_max)
             assert rel_rms < layer_rms_tol and rel_max < layer_max_tol, (cfg.name, "layer", l, "sequence", b,
                                                                          rel_rms, rel_max)
+            # ... and it must look like rounding noise everywhere: no row and no block of 128 columns
+            # carries much more of it than the rest (a wrong tile, head or split would)
+            e2 = (got[b] - ref).pow(2)
+            overall = e2.mean().sqrt().item()
+            row_ratio = e2.mean(dim=1).sqrt().max().item() / overall
+            blk_ratio = e2.view(R, -1, 128).mean(dim=(0, 2)).sqrt().max().item() / overall
+            worst["row"], worst["blk"] = max(worst["row"], row_ratio), max(worst["blk"], blk_ratio)
+            # (observed over all layers: rows up to 3.0x, blocks up to 1.16x; two weight rows swapped inside
+            # one 128-column block of the down projection, planted in an fp32 copy of the oracle's layer on
+            # the CPU, move the overall error from 2.47e-3 to 2.55e-3 of the rms but that block to 2.2x)
+            assert row_ratio < 4.5 and blk_ratio < 1.5, (cfg.name, "layer", l, "sequence", b, row_ratio, blk_ratio)
             gk = kc[b, :, L:L + R, :].float().cpu().double().permute(1, 0, 2)
             gv = vc[b, :, :, L:L + R].float().cpu().double().permute(2, 0, 1)
             for name, g_t, r_t in (("k", gk, k_new), ("v", gv, v_new)):
@@ -115,7 +128,8 @@ def teacher_forced_depth(cfg, capsys, layer_rms_tol, layer_max_tol, min_clean, f
         del w, kp, vp
         if l % 4 == 3 or l == cfg.n_layers - 1:
             say(f"[{cfg.name}] layer {l + 1}/{cfg.n_layers}  worst so far: layer error / rms "
-                f"{worst['rms']:.2e} (max {worst['max']:.2e}), appended cache elements that differ "
+                f"{worst['rms']:.2e} (max {worst['max']:.2e}; noisiest row {worst['row']:.2f}x, noisiest 128-column block "
+                f"{worst['blk']:.2f}x the layer's rms error), appended cache elements that differ "
                 f"{worst['kv_flips']:.2e}" + (f", free-running drift / rms {worst['free_rms']:.2e}" if free_running else "")
                 + f"  [{time.time() - t0:.0f}s]")
 
