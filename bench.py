@@ -220,7 +220,7 @@ def graph_replay_ms(step, steps, warmup):
         return None
 
 
-def cpu_baseline(cfg, tokens_np, layers_sampled=1):
+def cpu_baseline(cfg, tokens_np, layers_sampled=2):
     """The oracle timed on this host on a bounded sample: `layers_sampled`
     decoder layers plus the LM head, row statistics and acceptance rule for the
     whole block; the full step is extrapolated as n_layers x layer + head."""
@@ -484,7 +484,7 @@ def main():
             fb.fly_lmhead_entropy_argmax(h5, model.w_lm, rs5, c5.vocab, o5.argmax.view(-1), o5.p_top1.view(-1),
                                          o5.h_norm.view(-1), None, ws5)
 
-        ms5 = time_region(lmhead5, 10, 3)
+        ms5 = time_region(lmhead5, 20, 5)
         fl5 = 2.0 * c5.M * c5.d * c5.vocab
         lm_mfma = {"workload": "c5_stress LM head + fused row statistics (1088 rows x 8192 x 128256)",
                    "bound": "mfma", "avg_launch_us": ms5 * 1e3, "flops_per_launch": fl5,
