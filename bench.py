@@ -353,6 +353,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c3_70b", choices=sorted(synth.CONFIGS))
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="override the number of sequences (other row counts of the same model shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--step-only", action="store_true",
                     help="only the timed step and the isolated gate/up and LM-head launches: no graph replay, "
@@ -381,6 +383,8 @@ def main():
     cfg = synth.CONFIGS[args.workload]
     if args.layers:
         cfg = cfg.replace(n_layers=args.layers)
+    if args.batch:
+        cfg = cfg.replace(name=f"{cfg.name}_batch{args.batch}", batch=args.batch)
 
     if args.roofline_only:
         roofline_only(cfg, args)

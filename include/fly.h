@@ -134,6 +134,8 @@ const char* fly_strerror(fly_status s);
  *                  2, 3, 4 or 6 = always, with workgroups of 128, 192, 256 or 384 rows
  *   "gemm_wide"    0 = the weight-streaming GEMM with 32-row tiles for 81..256 rows (automatic),
  *                  1 = never, 3, 4, 5, 6 or 8 = always, with that many 32-row tiles (M must fit)
+ *   "wide_phase"   the same GEMM: 1 = half of the waves request their loads after multiplying,
+ *                  2 = every wave before; 0 = automatic (1 from four row tiles on)
  *   "attn_splits"  cache splits per (sequence, KV head): 1..256; 0 = automatic
  *   "attn_block_tiles"  most 32-row query tiles per workgroup: 1..8; 0 = automatic (8)
  *   "target_wgs"   workgroups a launch aims for (default 256, one per compute unit)

@@ -581,7 +581,8 @@ const char* fly_strerror(fly_status s) {
 }
 
 // Tuning knobs for experiments: "gemm_nt" (1, 2, 4; 0 = automatic), "gemm_tiled", "gemm_wide",
-// "gemm_splits" (0 = automatic), "target_wgs" (workgroups a launch aims for).
+// "gemm_splits" (0 = automatic), "target_wgs" (workgroups a launch aims for), "wide_phase" (81..256-row
+// GEMM: 1 = half of the waves request their loads after multiplying, 2 = all before, 0 = automatic).
 fly_status fly_set_tuning(const char* key, int32_t value) {
   if (!key) return FLY_ERR_NULL_POINTER;
   if (!strcmp(key, "gemm_nt")) {
@@ -606,6 +607,9 @@ fly_status fly_set_tuning(const char* key, int32_t value) {
     if (value != 0 && value != 1 && value != 3 && value != 4 && value != 5 && value != 6 && value != 8)
       return FLY_ERR_BAD_SHAPE;
     g_wide = value;
+  } else if (!strcmp(key, "wide_phase")) {
+    if (value < 0 || value > 2) return FLY_ERR_BAD_SHAPE;
+    g_wide_phase = value;
   } else if (!strcmp(key, "target_wgs")) {
     if (value < 1) return FLY_ERR_BAD_SHAPE;
     g_target_wgs = value;

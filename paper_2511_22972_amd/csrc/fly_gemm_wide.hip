@@ -26,6 +26,8 @@
 // landed yet.)
 #include "fly_common.h"
 
+std::atomic<int> g_wide_phase{0};  // tuning knob: 0 automatic, 1 half of the waves late, 2 every wave early
+
 namespace {
 
 constexpr int WIDE_KC = 2;  // 32-wide k-tiles per chunk (pipeline step)
@@ -44,7 +46,7 @@ template <int MT, int EPI, int RING, int NWV, int CG>
 __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
     const bf16_t* __restrict__ X, const u32x4* __restrict__ Wp, void* __restrict__ out,
     const float* __restrict__ row_scale, int M, int N, int Kd, int chunks_per_split, int nblocks,
-    LmSample smp) {
+    int phase, LmSample smp) {
   constexpr int KC = WIDE_KC;
   constexpr int WGS = 2 * CG * NWV;  // 16-column strips per workgroup
   // Workgroups are dealt to the eight XCDs round-robin by linear id; consecutive
@@ -87,16 +89,17 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
     const int strip = min(strip0 + 2 * cg + (l32 >> 4), nstrips - 1);
     wbase[cg] = Wp + (int64_t)strip * ktiles * 64 + (lane & 15) + 16 * hi;
   }
+  auto load_w_kt = [&](u32x4 (&a)[CG][KC][2], int chunk, int kt) {
+    const int k = min(chunk * KC + kt, kt_last);
+#pragma unroll
+    for (int cg = 0; cg < CG; ++cg)
+#pragma unroll
+      for (int kh = 0; kh < 2; ++kh)
+        a[cg][kt][kh] = __builtin_nontemporal_load(wbase[cg] + (int64_t)k * 64 + 32 * kh);
+  };
   auto load_w = [&](u32x4 (&a)[CG][KC][2], int chunk) {
 #pragma unroll
-    for (int kt = 0; kt < KC; ++kt) {
-      const int k = min(chunk * KC + kt, kt_last);
-#pragma unroll
-      for (int cg = 0; cg < CG; ++cg)
-#pragma unroll
-        for (int kh = 0; kh < 2; ++kh)
-          a[cg][kt][kh] = __builtin_nontemporal_load(wbase[cg] + (int64_t)k * 64 + 32 * kh);
-    }
+    for (int kt = 0; kt < KC; ++kt) load_w_kt(a, chunk, kt);
   };
 
   // Activation pieces this wave copies per chunk: piece f = wave + NWV i is k-tile
@@ -162,6 +165,8 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
     for (int t = 0; t < BT; ++t)
       b[t] = __builtin_bit_cast(bf16x8, xs[stage][kt][2 * (t0 + t) + (l32 >> 4)][4 * r + (c ^ ((r >> 2) & 3))]);
   };
+  // One chunk of multiplies (the activation fragments of group g+1 are requested from LDS
+  // before the multiplies of group g; the scheduling barriers pin that order).
   auto compute = [&](const u32x4 (&a)[CG][KC][2], int chunk, int stage) {
     bf16x8 b[2][BT];
     read_b(b[0], stage, 0);
@@ -185,30 +190,39 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
     }
   };
 
-  // Software pipeline over k-chunks.  Weights: a ring of RING register buffers;
-  // while chunk c is multiplied, chunks c+1 .. c+RING-1 are in flight.
-  // Activations: step c requests chunk c+2 into one of two register buffers,
-  // multiplies chunk c out of LDS stage c % 2 and then writes chunk c+1 (requested in
-  // step c-1) from the other register buffer into stage (c+1) % 2, which every wave
-  // finished reading before the barrier that ended step c-1.  The wait for those
-  // registers leaves everything issued after them in flight: the weights requested in
-  // steps c-1 and c and the activations of chunk c+2.  The workgroup barrier is the bare
-  // instruction (a __syncthreads would also wait for every outstanding load); the
-  // explicit wait before it completes this wave's LDS writes and reads.
+  // Software pipeline over k-chunks: weights through a ring of RING register buffers,
+  // activations through two register buffers and two LDS stages; chunk c is multiplied
+  // out of LDS stage c % 2 while chunk c+1 is written to the other stage, which every
+  // wave finished reading before the barrier that ended step c-1.
+  //
+  // The eight waves of a workgroup leave that barrier together and share one address unit,
+  // which takes ~25 cycles per 1 KiB load (measured: busy 1390 cycles per step of 56 loads,
+  // against 1280 cycles of matrix work per SIMD and 2760 cycles per step), and a wave issues
+  // in order: while all eight request their loads nobody multiplies.  So half of the waves
+  // may run out of phase with the other half: they multiply first and request afterwards.
+  //   early waves, step c: request activations c+2 and weights c+RING-1 (into the buffers
+  //     freed in step c-1), multiply chunk c, write activations c+1 to LDS, barrier.
+  //   late waves, step c: multiply chunk c, write activations c+1 to LDS, request
+  //     activations c+3 and weights c+RING into the buffers just freed, barrier.
+  // In both, the activations a step requests are older than its weights, so the wait that
+  // precedes the LDS write (for a buffer requested two steps before it is written) never
+  // covers the weight loads issued since.  The workgroup barrier is the bare instruction
+  // (a __syncthreads would also wait for every outstanding load); the explicit wait before
+  // it completes this wave's LDS writes and reads.  Both paths pass the same barriers.
   u32x4 ring[RING][CG][KC][2];
   u32x4 xb[2][NXL];
-  auto step = [&](const u32x4 (&cur)[CG][KC][2], u32x4 (&refill)[CG][KC][2], u32x4 (&xnew)[NXL],
-                  const u32x4 (&xnext)[NXL], int chunk) {
-    load_x(xnew, chunk + 2);
-    __builtin_amdgcn_sched_barrier(0);
-    load_w(refill, chunk + RING - 1);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(cur, chunk, (chunk - chunk_begin) & 1);
-    store_x(xnext, (chunk - chunk_begin + 1) & 1);
-    FLY_WAIT_LGKMCNT0();
-    FLY_BARE_BARRIER();
-  };
-  if (chunk_begin < chunk_end) {
+  auto run_early = [&]() {
+    auto step = [&](const u32x4 (&cur)[CG][KC][2], u32x4 (&refill)[CG][KC][2], u32x4 (&xnew)[NXL],
+                    const u32x4 (&xnext)[NXL], int chunk) {
+      load_x(xnew, chunk + 2);
+      __builtin_amdgcn_sched_barrier(0);
+      load_w(refill, chunk + RING - 1);
+      __builtin_amdgcn_sched_barrier(0);
+      compute(cur, chunk, (chunk - chunk_begin) & 1);
+      store_x(xnext, (chunk - chunk_begin + 1) & 1);
+      FLY_WAIT_LGKMCNT0();
+      FLY_BARE_BARRIER();
+    };
     load_x(xb[0], chunk_begin);
     load_x(xb[1], chunk_begin + 1);
     __builtin_amdgcn_sched_barrier(0);
@@ -227,6 +241,50 @@ __global__ __launch_bounds__(64 * NWV) void gemm_bf16_wide_kernel(
 #pragma unroll
     for (int r = 0; r < RING - 1; ++r)
       if (c + r < chunk_end) step(ring[r], ring[(r + RING - 1) % RING], xb[r & 1], xb[(r + 1) & 1], c + r);
+  };
+  auto run_late = [&]() {
+    auto step = [&](u32x4 (&cur)[CG][KC][2], u32x4 (&xnext)[NXL], int chunk) {
+      compute(cur, chunk, (chunk - chunk_begin) & 1);
+      store_x(xnext, (chunk - chunk_begin + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      load_x(xnext, chunk + 3);
+      __builtin_amdgcn_sched_barrier(0);
+      load_w(cur, chunk + RING);
+      __builtin_amdgcn_sched_barrier(0);
+      FLY_WAIT_LGKMCNT0();
+      FLY_BARE_BARRIER();
+    };
+    load_x(xb[0], chunk_begin);
+    load_x(xb[1], chunk_begin + 1);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int r = 0; r < RING; ++r) load_w(ring[r], chunk_begin + r);
+    store_x(xb[0], 0);
+    __builtin_amdgcn_sched_barrier(0);
+    load_x(xb[0], chunk_begin + 2);
+    __builtin_amdgcn_sched_barrier(0);
+    FLY_WAIT_LGKMCNT0();
+    FLY_BARE_BARRIER();
+    int c = chunk_begin;
+    while (c + RING <= chunk_end) {
+#pragma unroll
+      for (int r = 0; r < RING; ++r) step(ring[r], xb[(r + 1) & 1], c + r);
+      c += RING;
+    }
+#pragma unroll
+    for (int r = 0; r < RING - 1; ++r)
+      if (c + r < chunk_end) step(ring[r], xb[(r + 1) & 1], c + r);
+  };
+  // Half of the waves run late (phase 1).  Measured at the 405B width, gate/up GEMM, same box:
+  // 136 rows 744 -> 702 us, 102 rows 641 -> 606, 170 rows 835 -> 797, 238 rows 1004 -> 965; at
+  // 85 rows (three row tiles, where the weight stream alone sets the time) 580 -> 597, so the
+  // launcher keeps every wave early there.  Which half is late makes no difference (waves
+  // w < 4 or odd w: 702 and 703 us).
+  if (chunk_begin < chunk_end) {
+    if (phase == 1 && wave < NWV / 2)
+      run_late();
+    else
+      run_early();
   }
 
   // ---- epilogues.  Accumulator register r of tile (cg, t) in lane l is
@@ -316,18 +374,20 @@ static hipError_t launch_wide_mt(const bf16_t* X, const bf16_t* Wp, void* out, c
   const int cps = (nchunks + plan.splits - 1) / plan.splits;
   dim3 grid(nblocks, plan.splits, 1), block(64 * NWV);
   const u32x4* W4 = (const u32x4*)Wp;
+  const int knob = g_wide_phase.load();
+  const int phase = knob == 0 ? (MT >= 4 ? 1 : 2) : knob;
   if (epi == EPI_PARTIAL)
     hipLaunchKernelGGL((gemm_bf16_wide_kernel<MT, EPI_PARTIAL, RING, NWV, CG>), grid, block, 0, st, X, W4, out,
-                       row_scale, M, N, Kd, cps, nblocks, smp);
+                       row_scale, M, N, Kd, cps, nblocks, phase, smp);
   else if (epi == EPI_SWIGLU)
     hipLaunchKernelGGL((gemm_bf16_wide_kernel<MT, EPI_SWIGLU, RING, NWV, CG>), grid, block, 0, st, X, W4, out,
-                       row_scale, M, N, Kd, cps, nblocks, smp);
+                       row_scale, M, N, Kd, cps, nblocks, phase, smp);
   else if (epi == EPI_LMHEAD)
     hipLaunchKernelGGL((gemm_bf16_wide_kernel<MT, EPI_LMHEAD, RING, NWV, CG>), grid, block, 0, st, X, W4, out,
-                       row_scale, M, N, Kd, cps, nblocks, smp);
+                       row_scale, M, N, Kd, cps, nblocks, phase, smp);
   else
     hipLaunchKernelGGL((gemm_bf16_wide_kernel<MT, EPI_LMSAMPLE, RING, NWV, CG>), grid, block, 0, st, X, W4, out,
-                       row_scale, M, N, Kd, cps, nblocks, smp);
+                       row_scale, M, N, Kd, cps, nblocks, phase, smp);
   return hipGetLastError();
 }
 

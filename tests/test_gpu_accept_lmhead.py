@@ -156,15 +156,19 @@ def test_lmhead_bf16_many_rows(fb, M, d, V):
                                          (192, 32, 16, 6), (200, 320, 4096 + 16, 0), (256, 64, 272, 8),
                                          (97, 160, 528, 5), (140, 128, 256, 8), (81, 256, 2048 + 48, 0),
                                          (96, 96, 16 * 131, 3), (128, 544, 1040, 4), (110, 64, 272, 0)])
-def test_lmhead_bf16_wide_rows(fb, M, d, V, tiles):
+@pytest.mark.parametrize("phase", [1, 2])
+def test_lmhead_bf16_wide_rows(fb, M, d, V, tiles, phase):
     """81..256 rows take the weight-streaming kernel with 32 x 32 tiles (3 to 8 row tiles per
     wave): ragged last tile, a vocabulary that is not a multiple of the 256-column block, an odd
-    number of k-tiles, fewer chunks than the register ring is deep."""
+    number of k-tiles, fewer chunks than the register ring is deep; with half of the waves
+    requesting their loads after multiplying (phase 1) and with every wave requesting first (2)."""
     fb.fly_set_tuning("gemm_wide", tiles)
+    fb.fly_set_tuning("wide_phase", phase)
     try:
         got, ref = lmhead_case(fb, M, d, V, "bf16", hidden_std=4.0, seed=5)
     finally:
         fb.fly_set_tuning("gemm_wide", 0)
+        fb.fly_set_tuning("wide_phase", 0)
     check_lmhead(got, ref, 2e-3)
 
 

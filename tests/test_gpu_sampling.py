@@ -86,12 +86,15 @@ def test_sample_bf16_nine_tile_streaming_kernel(fb):
 
 @pytest.mark.parametrize("M,d,V,tiles", [(129, 256, 2048 + 48, 0), (160, 96, 16 * 131, 5), (161, 544, 1040, 6),
                                          (256, 64, 272, 8), (96, 96, 16 * 131, 3), (128, 544, 1040, 4)])
-def test_sample_bf16_wide_kernel(fb, M, d, V, tiles):
+@pytest.mark.parametrize("phase", [1, 2])
+def test_sample_bf16_wide_kernel(fb, M, d, V, tiles, phase):
     fb.fly_set_tuning("gemm_wide", tiles)
+    fb.fly_set_tuning("wide_phase", phase)
     try:
         res = sample_case(fb, M, d, V, "bf16", SEED, OFFSET, data_seed=5)
     finally:
         fb.fly_set_tuning("gemm_wide", 0)
+        fb.fly_set_tuning("wide_phase", 0)
     check_sample(*res)
 
 

@@ -341,15 +341,18 @@ def test_gateup_swiglu_stage_bf16_many_rows():
 
 
 @pytest.mark.gpu
-def test_gateup_swiglu_stage_bf16_wide_rows():
+@pytest.mark.parametrize("phase", [1, 2])
+def test_gateup_swiglu_stage_bf16_wide_rows(phase):
     """The same stage at 129..256 rows (weight-streaming kernel with 32 x 32 tiles), every
-    row-tile count, ragged rows / columns / k-tiles."""
+    row-tile count, ragged rows / columns / k-tiles; with half of the waves requesting their
+    loads after multiplying (phase 1) and with every wave requesting first (phase 2)."""
     from paper_2511_22972_amd import binding as fb
     cases = [(129, 256, 1056, 0), (160, 96, 16 * 37, 5), (161, 544, 512, 6), (192, 32, 16, 6),
              (200, 320, 2048 + 16, 0), (256, 64, 144, 8), (100, 160, 272, 5), (150, 1024, 256, 8),
              (81, 256, 1056, 0), (96, 96, 16 * 37, 3), (97, 544, 512, 0), (128, 320, 272, 4), (50, 64, 144, 3)]
     for M, d, F, tiles in cases:
         fb.fly_set_tuning("gemm_wide", tiles)
+        fb.fly_set_tuning("wide_phase", phase)
         x = synth.hash_normal(8, 320, (M, d), 1.0, torch.bfloat16, "cuda")
         wg = synth.hash_normal(8, 321, (d, F), 0.05, torch.bfloat16, "cuda")
         wu = synth.hash_normal(8, 322, (d, F), 0.05, torch.bfloat16, "cuda")
@@ -361,6 +364,7 @@ def test_gateup_swiglu_stage_bf16_wide_rows():
             fb.fly_gateup_swiglu(x, wp, a)
         finally:
             fb.fly_set_tuning("gemm_wide", 0)
+            fb.fly_set_tuning("wide_phase", 0)
         torch.cuda.synchronize()
         xd = x.float().cpu().double()
         ref = O.round_to_bf16(O.silu(xd @ wg.float().cpu().double()) * (xd @ wu.float().cpu().double()))
@@ -370,9 +374,10 @@ def test_gateup_swiglu_stage_bf16_wide_rows():
 
 
 @pytest.mark.gpu
-def test_projection_partials_bf16_wide_rows():
+@pytest.mark.parametrize("phase", [1, 2])
+def test_projection_partials_bf16_wide_rows(phase):
     """Split-K projection at 129..256 rows: the partial sums add up to x W (ragged last split,
-    more splits asked for than there are chunks)."""
+    more splits asked for than there are chunks; both orders of loads and multiplies)."""
     from paper_2511_22972_amd import binding as fb
     cases = [(136, 4096, 512, 0, 0), (200, 2048, 528, 0, 0), (256, 1056, 1040, 8, 0), (160, 2080, 256, 5, 5),
              (192, 96, 16, 6, 0), (129, 3072, 272, 0, 7), (150, 1024, 256, 6, 16),
@@ -380,6 +385,7 @@ def test_projection_partials_bf16_wide_rows():
     for M, Kd, N, tiles, force_splits in cases:
         fb.fly_set_tuning("gemm_wide", tiles)
         fb.fly_set_tuning("gemm_splits", force_splits)
+        fb.fly_set_tuning("wide_phase", phase)
         x = synth.hash_normal(9, 330, (M, Kd), 1.0, torch.bfloat16, "cuda")
         w = synth.hash_normal(9, 331, (Kd, N), 0.05, torch.bfloat16, "cuda")
         wp = torch.empty(Kd * N, dtype=torch.bfloat16, device="cuda")
@@ -390,6 +396,7 @@ def test_projection_partials_bf16_wide_rows():
         finally:
             fb.fly_set_tuning("gemm_wide", 0)
             fb.fly_set_tuning("gemm_splits", 0)
+            fb.fly_set_tuning("wide_phase", 0)
         torch.cuda.synchronize()
         assert 1 <= splits <= 16
         got = partial[: splits * M * N].view(splits, M, N).double().sum(0).cpu()
