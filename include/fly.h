@@ -136,6 +136,8 @@ const char* fly_strerror(fly_status s);
  *                  1 = never, 3, 4, 5, 6 or 8 = always, with that many 32-row tiles (M must fit)
  *   "wide_phase"   the same GEMM: 1 = half of the waves request their loads after multiplying,
  *                  2 = every wave before; 0 = automatic (1 from four row tiles on)
+ *   "tiled_phase"  the LDS-tiled GEMM: 1 = the odd waves request their loads between the two halves
+ *                  of a step's multiplies, 2 = every wave first; 0 = automatic (1)
  *   "attn_splits"  cache splits per (sequence, KV head): 1..256; 0 = automatic
  *   "attn_block_tiles"  most 32-row query tiles per workgroup: 1..8; 0 = automatic (8)
  *   "target_wgs"   workgroups a launch aims for (default 256, one per compute unit)

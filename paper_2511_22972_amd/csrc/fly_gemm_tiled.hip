@@ -11,7 +11,11 @@
 // x 32 WM WGM rows.  Global memory is copied straight into LDS by the LDS-direct
 // loads (no staging registers) into a ring of NS k-steps of 32, with one
 // barrier per k-step.
+#include <type_traits>
+
 #include "fly_common.h"
+
+std::atomic<int> g_tiled_phase{0};  // tuning knob: 0 automatic, 1 half of the waves request mid-step, 2 every wave first
 
 namespace {
 
@@ -70,7 +74,7 @@ template <int WGN, int WGM, int WM, int EPI, int NS>
 __global__ __launch_bounds__(WGN* WGM * 64) void gemm_bf16_tiled_kernel(
     const bf16_t* __restrict__ X, const u32x4* __restrict__ Wp, void* __restrict__ out,
     const float* __restrict__ row_scale, int M, int N, int Kd, int kt_per_split, int nblocks,
-    int mblocks, LmSample smp) {
+    int mblocks, int phase, LmSample smp) {
   constexpr int NW = WGN * WGM;                // waves
   constexpr int WLOADS = 8 * WGN / NW;         // LDS-direct loads per wave and stage: weights
   constexpr int XLOADS = 2 * WM * WGM / NW;    //                                      activations
@@ -138,22 +142,38 @@ __global__ __launch_bounds__(WGN* WGM * 64) void gemm_bf16_tiled_kernel(
   // Step c: wait for this wave's loads of stage c (the NS-2 younger stages may
   // still be in flight); barrier (everyone's loads of stage c have landed and
   // everyone is done reading stage c-1); refill the slot of stage c-1 with
-  // stage c+NS-1; multiply stage c.
-  int cur = 0, refill = NS - 1;
-  for (int c = 0; c < nst; ++c) {
-    FLY_WAIT_VMCNT((NS - 2) * LPW);
-    FLY_BARE_BARRIER();
-    issue_loads(refill, kt_begin + c + NS - 1);
-    TiledFrags<WM> f;
-    tiled_read_frags<WGN, WGM, WM>(&ring[cur], f, 0, wn, wm, lane);
-    tiled_mma<WM>(f, acc);
-    tiled_read_frags<WGN, WGM, WM>(&ring[cur], f, 1, wn, wm, lane);
-    tiled_mma<WM>(f, acc);
-    FLY_WAIT_LGKMCNT0();
-    __builtin_amdgcn_sched_barrier(0);
-    refill = cur;
-    cur = cur + 1 == NS ? 0 : cur + 1;
-  }
+  // stage c+NS-1; multiply stage c.  The eight waves leave the barrier together and
+  // share one address unit (~25 cycles per 1 KiB load, 40 loads per step), and a wave
+  // issues in order: a wave that requests first multiplies only once its loads are
+  // accepted.  Half of the waves (LATE) therefore request their share between the two
+  // halves of the step's multiplies; the slot they refill is free for the whole step,
+  // and the number of younger loads at the wait is the same.
+  auto steps = [&](auto late_c) {
+    constexpr bool LATE = decltype(late_c)::value;
+    int cur = 0, refill = NS - 1;
+    for (int c = 0; c < nst; ++c) {
+      FLY_WAIT_VMCNT((NS - 2) * LPW);
+      FLY_BARE_BARRIER();
+      if constexpr (!LATE) issue_loads(refill, kt_begin + c + NS - 1);
+      TiledFrags<WM> f;
+      tiled_read_frags<WGN, WGM, WM>(&ring[cur], f, 0, wn, wm, lane);
+      tiled_mma<WM>(f, acc);
+      if constexpr (LATE) issue_loads(refill, kt_begin + c + NS - 1);
+      tiled_read_frags<WGN, WGM, WM>(&ring[cur], f, 1, wn, wm, lane);
+      tiled_mma<WM>(f, acc);
+      FLY_WAIT_LGKMCNT0();
+      __builtin_amdgcn_sched_barrier(0);
+      refill = cur;
+      cur = cur + 1 == NS ? 0 : cur + 1;
+    }
+  };
+  // Measured on the 1088 x 8192 x 128256 LM head, same box: every wave first 2140-2180 us, odd
+  // waves late 2045-2070; the upper half of the waves late 2092, late after a quarter or three
+  // quarters of the multiplies 2051-2073, four groups of waves at the four quarters 2136-2145.
+  if (phase == 1 && (wave & 1))
+    steps(std::true_type{});
+  else
+    steps(std::false_type{});
   FLY_WAIT_VMCNT(0);  // surplus (clamped) loads must have landed before the wave may end
 
   // ---- epilogues.  Accumulator register r of tile (i, t) in lane l is
@@ -247,18 +267,20 @@ static hipError_t launch_tiled_shape(const bf16_t* X, const bf16_t* Wp, void* ou
   if (plan.mblocks * (32 * WM * WGM) < M) return hipErrorInvalidValue;
   dim3 grid((nblocks + 7) / 8 * 8 * plan.mblocks, plan.splits, 1), block(WGN * WGM * 64);
   const u32x4* W4 = (const u32x4*)Wp;
+  const int knob = g_tiled_phase.load();
+  const int phase = knob == 0 ? 1 : knob;
   if (epi == EPI_PARTIAL)
     hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WGN, WGM, WM, EPI_PARTIAL, NS>), grid, block, 0, st, X, W4,
-                       out, row_scale, M, N, Kd, kps, nblocks, plan.mblocks, smp);
+                       out, row_scale, M, N, Kd, kps, nblocks, plan.mblocks, phase, smp);
   else if (epi == EPI_SWIGLU)
     hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WGN, WGM, WM, EPI_SWIGLU, NS>), grid, block, 0, st, X, W4,
-                       out, row_scale, M, N, Kd, kps, nblocks, plan.mblocks, smp);
+                       out, row_scale, M, N, Kd, kps, nblocks, plan.mblocks, phase, smp);
   else if (epi == EPI_LMHEAD)
     hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WGN, WGM, WM, EPI_LMHEAD, NS>), grid, block, 0, st, X, W4,
-                       out, row_scale, M, N, Kd, kps, nblocks, plan.mblocks, smp);
+                       out, row_scale, M, N, Kd, kps, nblocks, plan.mblocks, phase, smp);
   else
     hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WGN, WGM, WM, EPI_LMSAMPLE, NS>), grid, block, 0, st, X, W4,
-                       out, row_scale, M, N, Kd, kps, nblocks, plan.mblocks, smp);
+                       out, row_scale, M, N, Kd, kps, nblocks, plan.mblocks, phase, smp);
   return hipGetLastError();
 }
 

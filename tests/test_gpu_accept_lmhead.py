@@ -143,12 +143,16 @@ def test_lmhead_bf16_many_rows(fb, M, d, V):
     prefetch ring is deep."""
     got, ref = lmhead_case(fb, M, d, V, "bf16", hidden_std=4.0)
     check_lmhead(got, ref, 2e-3)
-    for wm in (2, 3, 4, 6):
+    # every workgroup shape; two of them also with every wave requesting its loads first
+    # ("tiled_phase" 2; by default the odd waves request theirs in mid-step)
+    for wm, phase in ((2, 0), (3, 0), (4, 0), (6, 0), (3, 2), (6, 2)):
         fb.fly_set_tuning("gemm_tiled", wm)
+        fb.fly_set_tuning("tiled_phase", phase)
         try:
             got, ref = lmhead_case(fb, M, d, V, "bf16", hidden_std=4.0, seed=3)
         finally:
             fb.fly_set_tuning("gemm_tiled", 0)
+            fb.fly_set_tuning("tiled_phase", 0)
         check_lmhead(got, ref, 2e-3)
 
 

@@ -101,12 +101,14 @@ def test_sample_bf16_wide_kernel(fb, M, d, V, tiles, phase):
 @pytest.mark.parametrize("M,d,V", [(300, 544, 16 * 131), (1088, 512, 4096), (385, 96, 272)])
 def test_sample_bf16_tiled_kernel(fb, M, d, V):
     check_sample(*sample_case(fb, M, d, V, "bf16", SEED, OFFSET))
-    for wm in (2, 3, 4, 6):
+    for wm, phase in ((2, 0), (3, 0), (4, 0), (6, 0), (4, 2)):
         fb.fly_set_tuning("gemm_tiled", wm)
+        fb.fly_set_tuning("tiled_phase", phase)
         try:
             res = sample_case(fb, M, d, V, "bf16", SEED, OFFSET, data_seed=3)
         finally:
             fb.fly_set_tuning("gemm_tiled", 0)
+            fb.fly_set_tuning("tiled_phase", 0)
         check_sample(*res)
 
 

@@ -319,8 +319,10 @@ def test_gateup_swiglu_stage_bf16_many_rows():
     cases = [(M, d, F, 0) for M, d, F in ((200, 128, 16 * 37), (389, 256, 1056), (145, 32, 16), (1088, 64, 512))]
     cases += [(389, 256, 1056, shape) for shape in (2, 3, 4, 6)]
     cases += [(M, 256, 1056, shape) for M in (145, 200) for shape in (2, 3)]  # also where "wide" is the default
+    cases += [(389, 256, 1056, -shape) for shape in (2, 6)]  # negative: every wave requests its loads first
     for M, d, F, shape in cases:
-        fb.fly_set_tuning("gemm_tiled", shape)
+        fb.fly_set_tuning("gemm_tiled", abs(shape))
+        fb.fly_set_tuning("tiled_phase", 2 if shape < 0 else 0)
         x = synth.hash_normal(6, 320, (M, d), 1.0, torch.bfloat16, "cuda")
         wg = synth.hash_normal(6, 321, (d, F), 0.05, torch.bfloat16, "cuda")
         wu = synth.hash_normal(6, 322, (d, F), 0.05, torch.bfloat16, "cuda")
@@ -332,6 +334,7 @@ def test_gateup_swiglu_stage_bf16_many_rows():
             fb.fly_gateup_swiglu(x, wp, a)
         finally:
             fb.fly_set_tuning("gemm_tiled", 0)
+            fb.fly_set_tuning("tiled_phase", 0)
         torch.cuda.synchronize()
         xd = x.float().cpu().double()
         ref = O.round_to_bf16(O.silu(xd @ wg.float().cpu().double()) * (xd @ wu.float().cpu().double()))
