@@ -355,6 +355,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging)")
     ap.add_argument("--batch", type=int, default=0,
                     help="override the number of sequences (other row counts of the same model shape)")
+    ap.add_argument("--K", type=int, default=0, help="override the number of draft tokens per sequence")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--step-only", action="store_true",
                     help="only the timed step and the isolated gate/up and LM-head launches: no graph replay, "
@@ -385,6 +386,8 @@ def main():
         cfg = cfg.replace(n_layers=args.layers)
     if args.batch:
         cfg = cfg.replace(name=f"{cfg.name}_batch{args.batch}", batch=args.batch)
+    if args.K:
+        cfg = cfg.replace(name=f"{cfg.name}_K{args.K}", K=args.K)
 
     if args.roofline_only:
         roofline_only(cfg, args)

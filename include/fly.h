@@ -140,6 +140,8 @@ const char* fly_strerror(fly_status s);
  *                  of a step's multiplies, 2 = every wave first; 0 = automatic (1)
  *   "attn_splits"  cache splits per (sequence, KV head): 1..256; 0 = automatic
  *   "attn_block_tiles"  most 32-row query tiles per workgroup: 1..8; 0 = automatic (8)
+ *   "attn_phase"   1 = the odd waves request their share of the next cache stage after multiplying,
+ *                  2 = every wave first; 0 = automatic (1)
  *   "target_wgs"   workgroups a launch aims for (default 256, one per compute unit)
  * Workspace sizes depend on them: query again after a change.
  */

@@ -583,7 +583,8 @@ const char* fly_strerror(fly_status s) {
 // Tuning knobs for experiments: "gemm_nt" (1, 2, 4; 0 = automatic), "gemm_tiled", "gemm_wide",
 // "gemm_splits" (0 = automatic), "target_wgs" (workgroups a launch aims for), "wide_phase" (81..256-row
 // GEMM: 1 = half of the waves request their loads after multiplying, 2 = all before, 0 = automatic),
-// "tiled_phase" (LDS-tiled GEMM: 1 = odd waves request their loads in mid-step, 2 = all first, 0 = automatic).
+// "tiled_phase" (LDS-tiled GEMM: 1 = odd waves request their loads in mid-step, 2 = all first, 0 = automatic),
+// "attn_phase" (attention: 1 = odd waves request their stage loads after multiplying, 2 = all first, 0 = automatic).
 fly_status fly_set_tuning(const char* key, int32_t value) {
   if (!key) return FLY_ERR_NULL_POINTER;
   if (!strcmp(key, "gemm_nt")) {
@@ -614,6 +615,9 @@ fly_status fly_set_tuning(const char* key, int32_t value) {
   } else if (!strcmp(key, "tiled_phase")) {
     if (value < 0 || value > 2) return FLY_ERR_BAD_SHAPE;
     g_tiled_phase = value;
+  } else if (!strcmp(key, "attn_phase")) {
+    if (value < 0 || value > 2) return FLY_ERR_BAD_SHAPE;
+    g_attn_phase = value;
   } else if (!strcmp(key, "target_wgs")) {
     if (value < 1) return FLY_ERR_BAD_SHAPE;
     g_target_wgs = value;

@@ -324,7 +324,7 @@ struct AttnPlan {
   int block_tiles; // 32-row tiles per query block (1..8)
 };
 extern std::atomic<int> g_attn_force_splits, g_attn_force_block_tiles;
-extern std::atomic<int> g_wide_phase, g_tiled_phase;
+extern std::atomic<int> g_wide_phase, g_tiled_phase, g_attn_phase;
 AttnPlan plan_attention(int B, int K, int Hq, int Hkv, int max_total_len);
 size_t attention_workspace_floats(int B, int K, int Hq, int Hkv, int hd, const AttnPlan& p);
 hipError_t launch_attention_bf16(const bf16_t* q, const bf16_t* kcache, const bf16_t* vcache,

@@ -251,12 +251,14 @@ ATTENTION_STAGE_CASES = [
 ]
 
 
+@pytest.mark.parametrize("phase", [1, 2])
 @pytest.mark.parametrize("hq,hkv,K,block_tiles", ATTENTION_STAGE_CASES)
-def test_attention_stage_bf16(hq, hkv, K, block_tiles):
+def test_attention_stage_bf16(hq, hkv, K, block_tiles, phase):
     """fly_attention alone on seeded q and cache: one rounding (the bf16 output)
     separates the two sides, so elements agree to one bf16 ulp and almost all
     are identical.  Covers ragged lengths, a cache that ends mid-tile, several
-    cache splits, and every way the query tiles are dealt to waves and workgroups."""
+    cache splits, every way the query tiles are dealt to waves and workgroups, and both
+    points of a step at which a wave requests its share of the next cache stage."""
     from paper_2511_22972_amd import binding as fb
     cfg = synth.CONFIGS["c3_70b"].replace(n_layers=1, n_q_heads=hq, n_kv_heads=hkv, batch=3, K=K,
                                           kv_len=1000)
@@ -270,11 +272,13 @@ def test_attention_stage_bf16(hq, hkv, K, block_tiles):
     q = synth.hash_normal(cfg.seed, 310, (cfg.M, cfg.q_dim), 2.0, torch.bfloat16, "cuda")
     o = torch.zeros_like(q)
     fb.fly_set_tuning("attn_block_tiles", block_tiles)
+    fb.fly_set_tuning("attn_phase", phase)
     try:
         ws = fb.alloc_workspace(fb.fly_workspace_bytes(desc, cfg.batch, cfg.K, max(kv_lens)))
         fb.fly_attention(desc, kv, 0, q, o, cfg.batch, cfg.K, ws)
     finally:
         fb.fly_set_tuning("attn_block_tiles", 0)
+        fb.fly_set_tuning("attn_phase", 0)
     torch.cuda.synchronize()
     got = o.float().cpu().double().view(cfg.batch, R, cfg.n_q_heads, cfg.head_dim)
     num = O.Numerics("bf16")
